@@ -1,0 +1,154 @@
+/* sagekv.h - C ABI of the MI355X (gfx950) SAGE-KV hot path.
+ *
+ * SAGE-KV (arXiv 2503.08879, Sec. 2) compresses a model's KV cache once, after
+ * prefill: per layer and head it keeps the first tokens (sink), the most recent
+ * tokens and the top-k of the tokens in between, ranked by the attention score
+ * of the LAST token's query; decoding then attends over that reduced cache, and
+ * every generated token enters the recent window, which evicts its oldest entry.
+ *
+ * Conventions
+ *   - Every data pointer is DEVICE memory owned by the caller (unless a comment
+ *     says host).  Descriptors are host structs, read during the call only.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, null =
+ *     the default stream).  No call allocates, frees or synchronises.
+ *   - Indices are 0-based.  A "problem" is one layer of one sequence; problems are
+ *     independent (Sec. 2: selection is done "for each layer").  A "row" is one
+ *     (problem, KV head).  G = n_q_heads / n_kv_heads consecutive query heads share
+ *     KV head c = h / G (App. A.2's query group number).
+ *   - n_recent counts the last prompt token: in the paper's Step 1 notation
+ *     n_recent = R + 1, n_sink = S, and L = N.  Candidates for eviction are the
+ *     positions [n_sink, L - n_recent).
+ *   - Errors are return codes.  Arguments are checked before anything is launched:
+ *     on SAGEKV_ERR_INVALID_ARG / _UNSUPPORTED / _WORKSPACE nothing was written.
+ *   - Element types: bf16 (raw 16-bit patterns) or fp32; head_dim 64 or 128; the
+ *     innermost (head_dim) stride is 1 and rows must be 16-byte aligned.
+ */
+#ifndef SAGEKV_H
+#define SAGEKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SAGEKV_OK = 0,
+  SAGEKV_ERR_INVALID_ARG = 1,
+  SAGEKV_ERR_UNSUPPORTED = 2,
+  SAGEKV_ERR_WORKSPACE = 3,
+  SAGEKV_ERR_DEVICE = 4
+} sagekv_status;
+
+typedef enum { SAGEKV_BF16 = 0, SAGEKV_F32 = 1 } sagekv_dtype;
+
+/* How the G query heads of a KV head are combined before the top-k (Sec. 2 Step 2,
+ * "Hq groups of the top-k"; App. A.2).
+ *   GROUP_SUM: the heads' softmax probabilities are added and the KV head takes ONE
+ *              top-k (the paper prints no operator for this; it is this library's
+ *              primary mode).
+ *   PER_QUERY: every query head takes its own top-k, the KV head stores G lists
+ *              (the paper's literal rule).  Not implemented on the GPU yet:
+ *              SAGEKV_ERR_UNSUPPORTED. */
+typedef enum { SAGEKV_HEADS_GROUP_SUM = 0, SAGEKV_HEADS_PER_QUERY = 1 } sagekv_head_mode;
+
+/* ---- eviction pass ------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_problems;          /* layers x sequences                                       */
+  int32_t n_q_heads;           /* Hq                                                       */
+  int32_t n_kv_heads;          /* Hkv, divides Hq                                          */
+  int32_t head_dim;            /* 64 or 128                                                */
+  int32_t dtype;               /* sagekv_dtype of q_last, K, V, Kc, Vc                     */
+  int32_t head_mode;           /* sagekv_head_mode                                         */
+  int64_t L;                   /* cache length, last prompt token included                 */
+  int64_t k_stride_problem;    /* strides of K in ELEMENTS: K[p][c][i][j] is at            */
+  int64_t k_stride_head;       /*   p*stride_problem + c*stride_head + i*stride_token + j  */
+  int64_t k_stride_token;
+  int64_t v_stride_problem;    /* the same three for V                                     */
+  int64_t v_stride_head;
+  int64_t v_stride_token;
+  int32_t n_sink;              /* S >= 0                                                   */
+  int32_t n_recent;            /* W >= 1, includes the last token                          */
+  int32_t k;                   /* middle tokens kept per row, 0 <= k <= L - S - W          */
+  int32_t compact_capacity;    /* row pitch (tokens) of Kc / Vc, >= S + k + W              */
+} sagekv_select_desc;
+
+/* Bytes of device scratch sagekv_select needs for this descriptor (0 if it is invalid). */
+size_t sagekv_select_workspace_bytes(const sagekv_select_desc* desc);
+
+/* Sec. 2 Steps 1-3.  For every row:
+ *   score[i] = sum over the row's G query heads of softmax_i( q_last[h] . K[i] / sqrt(head_dim) ),
+ *              the softmax taken over the whole row i in [0, L);
+ *   sel      = the k candidates with the largest score (equal scores: lower index first),
+ *              in ascending position;
+ *   kept     = [0, S) ++ sel ++ [L - W, L);     Kc[t] = K[kept[t]],  Vc[t] = V[kept[t]].
+ * In:  q_last [n_problems, Hq, head_dim] contiguous; K, V strided as described above (read only).
+ * Out: Kc, Vc [n_problems, Hkv, compact_capacity, head_dim] contiguous, rows [0, S+k+W) written;
+ *      kept_idx [n_problems, Hkv, S+k+W] int32;
+ *      scores_out (nullable) [n_problems, Hkv, L] fp32 (the scores the selection used).
+ * Scores are computed in fp32; the candidates close to the k-th score are re-evaluated in
+ * fp64 before the final decision, so the kept set does not depend on fp32 summation order. */
+sagekv_status sagekv_select(const sagekv_select_desc* desc, const void* q_last, const void* K, const void* V,
+                            void* Kc, void* Vc, int32_t* kept_idx, float* scores_out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream);
+
+/* ---- decoding over the reduced cache -------------------------------------------------- */
+typedef struct {
+  int32_t n_problems, n_q_heads, n_kv_heads, head_dim;
+  int32_t dtype;               /* of q, k_new, v_new, Kc, Vc                                */
+  int32_t head_mode;           /* GROUP_SUM only                                            */
+  int32_t n_sink, k, n_recent; /* layout of a reduced row: [sink | selected | recent window] */
+  int32_t compact_capacity;    /* row pitch of Kc / Vc                                      */
+  int32_t grow_recent;         /* 0: the paper's fixed-size FIFO window (Step 4)            */
+                               /* 1: nothing is evicted, new tokens go to rows S+k+W, ...   */
+} sagekv_decode_desc;
+
+/* Step 4's cache update: put (k_new, v_new) [n_problems, Hkv, head_dim] into every reduced row.
+ * `n_appended` = how many tokens were appended to this cache before this call (host counter).
+ * FIFO: the window is a ring; the new token overwrites its oldest entry, physical slot
+ *       S + k + (n_appended mod W).  Attention does not depend on the physical order.
+ * grow: slot S + k + W + n_appended, which must be < compact_capacity. */
+sagekv_status sagekv_append(const sagekv_decode_desc* desc, const void* k_new, const void* v_new, void* Kc,
+                            void* Vc, int32_t n_appended, void* hip_stream);
+
+size_t sagekv_decode_workspace_bytes(const sagekv_decode_desc* desc);
+
+/* Zero-fills a decode workspace.  Required once before its first use; every decode call
+ * leaves the workspace ready for the next one. */
+sagekv_status sagekv_decode_workspace_init(const sagekv_decode_desc* desc, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream);
+
+/* Step 4's attention: out[h] = sum_t softmax_t( q[h] . Kc[c][t] / sqrt(head_dim) ) Vc[c][t],
+ * t in [0, len), c = h / G.   q [n_problems, Hq, head_dim]; out [n_problems, Hq, head_dim] fp32.
+ * 1 <= len <= compact_capacity. */
+sagekv_status sagekv_decode_attn(const sagekv_decode_desc* desc, const void* q, const void* Kc, const void* Vc,
+                                 int32_t len, float* out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
+/* One whole decode step in a single launch: sagekv_append(k_new, v_new, n_appended) followed by
+ * sagekv_decode_attn over the updated cache (the new token attends to itself).  The length
+ * attended is S+k+W (FIFO) or S+k+W+n_appended+1 (grow). */
+sagekv_status sagekv_decode_step(const sagekv_decode_desc* desc, const void* q, const void* k_new,
+                                 const void* v_new, void* Kc, void* Vc, int32_t n_appended, float* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- misc ---------------------------------------------------------------------------------- */
+const char* sagekv_status_string(sagekv_status s); /* host string, static storage */
+
+/* Stage timing for benchmarks (host-side state, per process; not thread safe).
+ * sagekv_stage_timing_enable(n) creates HIP events for the next n instrumented calls of
+ * sagekv_select and n of sagekv_decode_attn / sagekv_decode_step (n = 0 switches it off and
+ * destroys the events).  While enabled, each call records an event pair around every stage's
+ * launches on the call's own stream.  sagekv_stage_timing_read(which, call, ms) waits for that
+ * call's events and returns the elapsed milliseconds per stage: which = 0 reads a select call
+ * (ms[SAGEKV_STAGE_SCORE .. SAGEKV_STAGE_GATHER]), which = 1 a decode call (ms[0] only). */
+enum { SAGEKV_STAGE_SCORE = 0, SAGEKV_STAGE_STATS = 1, SAGEKV_STAGE_COMBINE = 2, SAGEKV_STAGE_TOPK = 3,
+       SAGEKV_STAGE_GATHER = 4, SAGEKV_N_STAGES = 5 };
+sagekv_status sagekv_stage_timing_enable(int32_t n_calls);
+sagekv_status sagekv_stage_timing_read(int32_t which, int32_t call, float* ms /* host */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,184 @@
+"""Thin ctypes binding of libsagekv.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  torch is used for device
+memory (tensors are passed as raw device pointers) and for the current stream handle.
+The binding fails loudly when the built library is missing; there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsagekv.so")
+
+BF16, F32 = 0, 1
+GROUP_SUM, PER_QUERY = 0, 1
+STAGES = ("score", "stats", "combine", "topk", "gather")
+
+EXPORTS = (
+    "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_append",
+    "sagekv_decode_workspace_bytes", "sagekv_decode_workspace_init", "sagekv_decode_attn", "sagekv_decode_step",
+    "sagekv_stage_timing_enable", "sagekv_stage_timing_read",
+)
+
+
+class SelectDesc(ctypes.Structure):
+    _fields_ = [
+        ("n_problems", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("head_mode", ctypes.c_int32),
+        ("L", ctypes.c_int64),
+        ("k_stride_problem", ctypes.c_int64), ("k_stride_head", ctypes.c_int64), ("k_stride_token", ctypes.c_int64),
+        ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
+        ("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32), ("k", ctypes.c_int32),
+        ("compact_capacity", ctypes.c_int32),
+    ]
+
+
+class DecodeDesc(ctypes.Structure):
+    _fields_ = [
+        ("n_problems", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("head_mode", ctypes.c_int32),
+        ("n_sink", ctypes.c_int32), ("k", ctypes.c_int32), ("n_recent", ctypes.c_int32),
+        ("compact_capacity", ctypes.c_int32), ("grow_recent", ctypes.c_int32),
+    ]
+
+
+class SagekvError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {status_string(code)} (status {code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_08879_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.sagekv_status_string.restype = ctypes.c_char_p
+        L.sagekv_status_string.argtypes = [ctypes.c_int]
+        L.sagekv_select_workspace_bytes.restype = sz
+        L.sagekv_select_workspace_bytes.argtypes = [ctypes.POINTER(SelectDesc)]
+        L.sagekv_select.restype = ctypes.c_int
+        L.sagekv_select.argtypes = [ctypes.POINTER(SelectDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.sagekv_append.restype = ctypes.c_int
+        L.sagekv_append.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, i32, vp]
+        L.sagekv_decode_workspace_bytes.restype = sz
+        L.sagekv_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
+        L.sagekv_decode_workspace_init.restype = ctypes.c_int
+        L.sagekv_decode_workspace_init.argtypes = [ctypes.POINTER(DecodeDesc), vp, sz, vp]
+        L.sagekv_decode_attn.restype = ctypes.c_int
+        L.sagekv_decode_attn.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, i32, vp, vp, sz, vp]
+        L.sagekv_decode_step.restype = ctypes.c_int
+        L.sagekv_decode_step.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.sagekv_stage_timing_enable.restype = ctypes.c_int
+        L.sagekv_stage_timing_enable.argtypes = [i32]
+        L.sagekv_stage_timing_read.restype = ctypes.c_int
+        L.sagekv_stage_timing_read.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float)]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().sagekv_status_string(code).decode()
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    import torch
+
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_of(t) -> int:
+    import torch
+
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise SagekvError(code, what)
+
+
+# ---------------------------------------------------------------------------------------- select
+def select_desc(q_last, K, V, n_sink, n_recent, k, compact_capacity=None, head_mode=GROUP_SUM) -> SelectDesc:
+    """Descriptor for q_last [P,Hq,d] and K, V [P,Hkv,L,d] (any strides with a unit inner stride)."""
+    P, Hq, d = q_last.shape
+    _, Hkv, L, _ = K.shape
+    assert K.stride(3) == 1 and V.stride(3) == 1 and q_last.is_contiguous()
+    cap = n_sink + k + n_recent if compact_capacity is None else compact_capacity
+    return SelectDesc(P, Hq, Hkv, d, _dtype_of(K), head_mode, L, K.stride(0), K.stride(1), K.stride(2),
+                      V.stride(0), V.stride(1), V.stride(2), n_sink, n_recent, k, cap)
+
+
+def sagekv_select_workspace_bytes(desc: SelectDesc) -> int:
+    return lib().sagekv_select_workspace_bytes(ctypes.byref(desc))
+
+
+def sagekv_select(desc: SelectDesc, q_last, K, V, Kc, Vc, kept_idx, scores_out, workspace) -> None:
+    """Enqueue the eviction pass on torch's current stream.  All tensors are caller-allocated."""
+    code = lib().sagekv_select(ctypes.byref(desc), _ptr(q_last), _ptr(K), _ptr(V), _ptr(Kc), _ptr(Vc),
+                               _ptr(kept_idx), _ptr(scores_out), _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    _check(code, "sagekv_select")
+
+
+# ---------------------------------------------------------------------------------------- decode
+def decode_desc(n_problems, n_q_heads, n_kv_heads, head_dim, dtype, n_sink, k, n_recent, compact_capacity,
+                grow_recent=False, head_mode=GROUP_SUM) -> DecodeDesc:
+    return DecodeDesc(n_problems, n_q_heads, n_kv_heads, head_dim, dtype, head_mode, n_sink, k, n_recent,
+                      compact_capacity, int(grow_recent))
+
+
+def sagekv_decode_workspace_bytes(desc: DecodeDesc) -> int:
+    return lib().sagekv_decode_workspace_bytes(ctypes.byref(desc))
+
+
+def _ws_bytes(ws):
+    return 0 if ws is None else ws.numel() * ws.element_size()
+
+
+def sagekv_decode_workspace_init(desc: DecodeDesc, workspace) -> None:
+    _check(lib().sagekv_decode_workspace_init(ctypes.byref(desc), _ptr(workspace), _ws_bytes(workspace), _stream()),
+           "sagekv_decode_workspace_init")
+
+
+def sagekv_append(desc: DecodeDesc, k_new, v_new, Kc, Vc, n_appended: int) -> None:
+    _check(lib().sagekv_append(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _ptr(Kc), _ptr(Vc), n_appended,
+                               _stream()), "sagekv_append")
+
+
+def sagekv_decode_attn(desc: DecodeDesc, q, Kc, Vc, length: int, out, workspace) -> None:
+    _check(lib().sagekv_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(Kc), _ptr(Vc), length, _ptr(out),
+                                    _ptr(workspace), _ws_bytes(workspace), _stream()), "sagekv_decode_attn")
+
+
+def sagekv_decode_step(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, n_appended: int, out, workspace) -> None:
+    _check(lib().sagekv_decode_step(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(Kc), _ptr(Vc),
+                                    n_appended, _ptr(out), _ptr(workspace), _ws_bytes(workspace), _stream()),
+           "sagekv_decode_step")
+
+
+# ---------------------------------------------------------------------------------------- timing
+def sagekv_stage_timing_enable(n_calls: int) -> None:
+    _check(lib().sagekv_stage_timing_enable(n_calls), "sagekv_stage_timing_enable")
+
+
+def sagekv_stage_timing_read(which: int, call: int):
+    buf = (ctypes.c_float * len(STAGES))()
+    _check(lib().sagekv_stage_timing_read(which, call, buf), "sagekv_stage_timing_read")
+    return list(buf) if which == 0 else [buf[0]]

@@ -1,0 +1,139 @@
+// Device helpers for the gfx950 kernels: wave64 DPP reductions, typed 16-byte
+// loads, bf16 dot products, block scans.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sagekv {
+
+constexpr int kWave = 64;
+
+enum : int { DT_BF16 = 0, DT_F32 = 1 };
+
+// ---- element traits --------------------------------------------------------------------
+template <int DT>
+struct Elem;
+template <>
+struct Elem<DT_BF16> {
+  static constexpr int bytes = 2;
+  static constexpr int per_lane = 8;  // elements in one 16-byte load
+};
+template <>
+struct Elem<DT_F32> {
+  static constexpr int bytes = 4;
+  static constexpr int per_lane = 4;
+};
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+// 16 bytes of K (or V) against 16 bytes of q, accumulated in fp32.
+template <int DT>
+__device__ __forceinline__ float dot16(const uint4& a, const uint4& b, float acc);
+
+template <>
+__device__ __forceinline__ float dot16<DT_BF16>(const uint4& a, const uint4& b, float acc) {
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
+  return acc;
+}
+template <>
+__device__ __forceinline__ float dot16<DT_F32>(const uint4& a, const uint4& b, float acc) {
+  acc = fmaf(__uint_as_float(a.x), __uint_as_float(b.x), acc);
+  acc = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), acc);
+  acc = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), acc);
+  acc = fmaf(__uint_as_float(a.w), __uint_as_float(b.w), acc);
+  return acc;
+}
+
+// The 16 bytes of one lane as fp32 values (8 for bf16, 4 for fp32).
+template <int DT>
+__device__ __forceinline__ void unpack16(const uint4& a, float* f);
+template <>
+__device__ __forceinline__ void unpack16<DT_BF16>(const uint4& a, float* f) {
+  f[0] = bf16_lo(a.x); f[1] = bf16_hi(a.x); f[2] = bf16_lo(a.y); f[3] = bf16_hi(a.y);
+  f[4] = bf16_lo(a.z); f[5] = bf16_hi(a.z); f[6] = bf16_lo(a.w); f[7] = bf16_hi(a.w);
+}
+template <>
+__device__ __forceinline__ void unpack16<DT_F32>(const uint4& a, float* f) {
+  f[0] = __uint_as_float(a.x); f[1] = __uint_as_float(a.y); f[2] = __uint_as_float(a.z); f[3] = __uint_as_float(a.w);
+}
+
+__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void st16(void* p, const uint4& v) { *reinterpret_cast<uint4*>(p) = v; }
+
+// ---- cross-lane sums -----------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+// Sum over aligned groups of LANES consecutive lanes; every lane of the group gets the total.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(LANES == 1 || LANES == 2 || LANES == 4 || LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "");
+  if (LANES >= 2) v += dpp_f32<0xB1>(v);   // quad_perm [1,0,3,2]
+  if (LANES >= 4) v += dpp_f32<0x4E>(v);   // quad_perm [2,3,0,1]
+  if (LANES >= 8) v += dpp_f32<0x141>(v);  // row_half_mirror
+  if (LANES >= 16) v += dpp_f32<0x140>(v); // row_mirror
+  if (LANES >= 32) v += __shfl_xor(v, 16);
+  if (LANES >= 64) v += __shfl_xor(v, 32);
+  return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// exp(x) for x <= 0-ish via the hardware exp2, with the rounding error of x*log2(e) folded back in
+// (relative error a few 1e-7 down to x ~ -80).
+__device__ __forceinline__ float exp_accurate(float x) {
+  const float l2e_hi = 1.44269502162933349609375f;  // float(log2 e)
+  const float l2e_lo = 1.92596299112661746e-8f;     // log2 e - l2e_hi
+  float t = x * l2e_hi;
+  float e = fmaf(x, l2e_hi, -t);
+  e = fmaf(x, l2e_lo, e);
+  float r = __builtin_amdgcn_exp2f(t);
+  return fmaf(r, e * 0.693147182464599609375f, r);
+}
+
+__device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269502162933349609375f); }
+
+// ---- block-wide inclusive scan of one int per thread (blockDim.x = NT, multiple of 64) ---------
+// `wave_tot` is NT/64 ints of shared memory.  Returns the inclusive prefix; *total gets the block sum.
+template <int NT>
+__device__ __forceinline__ int block_scan_incl(int v, int* wave_tot, int* total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int x = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  __syncthreads();  // protects wave_tot against the previous use
+  if (lane == 63) wave_tot[w] = x;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) {
+    int t = wave_tot[i];
+    if (i < w) base += t;
+    tot += t;
+  }
+  *total = tot;
+  return x + base;
+}
+
+}  // namespace sagekv

@@ -1,0 +1,337 @@
+"""HIP path vs CPU oracle, element by element, through the C-ABI binding.  Needs an MI355X."""
+import numpy as np
+import pytest
+
+import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+BF16, F32 = synth.BF16, synth.F32
+GROUP_SUM = 0
+
+
+def rand_case(seed, P, Hq, Hkv, d, L, dtype):
+    key = synth.stream_key(seed, 55)
+    q = synth.fill_host(key, 0, P * Hq * d, dtype).reshape(P, Hq, d)
+    K = synth.fill_host(key, 1 << 30, P * Hkv * L * d, dtype).reshape(P, Hkv, L, d)
+    V = synth.fill_host(key, 1 << 32, P * Hkv * L * d, dtype).reshape(P, Hkv, L, d)
+    return q, K, V
+
+
+def select_parity(ref, dtype, q, K, V, S, W, k, cap=None):
+    out = gu.gpu_select(dtype, q, K, V, S, W, k, cap)
+    Kc, Vc, kept, s = ref.select(dtype, GROUP_SUM, q, K, V, S, W, k, cap, want_scores=True)
+    gu.check_scores(out["scores"], s[:, :, 0])
+    n_ex = gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k)
+    gu.check_gather(out, K, V, S, k, W)
+    if n_ex == 0:
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
+    return out, (Kc, Vc, kept, s)
+
+
+# ----------------------------------------------------------------------------- generator
+def test_device_fill_equals_host_fill():
+    import torch
+
+    for dtype, td in ((BF16, torch.bfloat16), (F32, torch.float32)):
+        key = synth.stream_key(4242, synth.T_K)
+        t = torch.empty(100_003, dtype=td, device="cuda")
+        synth.fill_device(t, key, 0)
+        np.testing.assert_array_equal(synth.torch_to_host(t, dtype), synth.fill_host(key, 0, 100_003, dtype))
+        t2 = torch.empty(4096, dtype=td, device="cuda")
+        synth.fill_device(t2, key, 12345 * 8)
+        np.testing.assert_array_equal(synth.torch_to_host(t2, dtype), synth.fill_host(key, 12345 * 8, 4096, dtype))
+
+
+def test_device_config_equals_host_config():
+    cfg = synth.CONFIGS["C1"]
+    q, K, V, pos = synth.kv_host(cfg)
+    qd, Kd, Vd, pos_d = synth.kv_device(cfg)
+    np.testing.assert_array_equal(synth.torch_to_host(Kd, cfg.dtype), K)
+    np.testing.assert_array_equal(synth.torch_to_host(Vd, cfg.dtype), V)
+    np.testing.assert_array_equal(synth.torch_to_host(qd, cfg.dtype), q)
+
+
+# ----------------------------------------------------------------------------- select
+def test_select_C1(ref):
+    cfg = synth.CONFIGS["C1"]
+    q, K, V, pos = synth.kv_host(cfg)
+    out, _ = select_parity(ref, cfg.dtype, q, K, V, cfg.n_sink, cfg.n_recent, cfg.k)
+    kept = out["kept"].reshape(cfg.rows, -1)
+    for r in range(cfg.rows):
+        assert set(pos[r].tolist()) <= set(kept[r].tolist())  # every needle survives
+
+
+@pytest.mark.parametrize(
+    "dtype,Hq,Hkv,d,L,S,W,k",
+    [
+        (BF16, 8, 2, 128, 5037, 4, 64, 300),     # G=4, ragged L (not a multiple of any tile)
+        (BF16, 7, 1, 128, 9001, 3, 17, 500),     # G=7 (Qwen group), odd everything
+        (BF16, 4, 4, 64, 4100, 0, 1, 100),       # G=1, d=64, no sink, window = last token only
+        (F32, 6, 2, 128, 3000, 5, 40, 123),      # fp32, d=128, G=3
+        (F32, 4, 2, 64, 1025, 4, 16, 64),        # fp32, d=64
+        (BF16, 16, 2, 128, 2050, 2, 30, 77),     # G=8
+        (BF16, 20, 2, 128, 1500, 2, 30, 77),     # G=10: two score launches per row
+    ],
+)
+def test_select_shapes(ref, dtype, Hq, Hkv, d, L, S, W, k):
+    q, K, V = rand_case(100 + Hq + L, 2, Hq, Hkv, d, L, dtype)
+    select_parity(ref, dtype, q, K, V, S, W, k, cap=S + k + W + 5)
+
+
+@pytest.mark.parametrize("k_kind", ["zero", "one", "E-1", "E"])
+def test_select_k_extremes(ref, k_kind):
+    P, Hq, Hkv, d, L, S, W = 1, 8, 2, 128, 1300, 4, 20
+    E = L - S - W
+    k = {"zero": 0, "one": 1, "E-1": E - 1, "E": E}[k_kind]
+    q, K, V = rand_case(7, P, Hq, Hkv, d, L, BF16)
+    out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
+    if k_kind == "E":
+        np.testing.assert_array_equal(out["Kc"], K)  # nothing evicted: the reduced cache IS the cache
+        np.testing.assert_array_equal(out["Vc"], V)
+    if k_kind == "zero":
+        assert out["kept"][0, 0].tolist() == list(range(S)) + list(range(L - W, L))
+
+
+def test_select_no_candidates(ref):
+    q, K, V = rand_case(8, 1, 4, 2, 64, 40, F32)
+    select_parity(ref, F32, q, K, V, 8, 32, 0)  # E = 0
+
+
+def test_select_all_scores_equal_takes_lowest_indices(ref):
+    """q = 0: every probability is 1/L, the whole row ties; the first k candidates must win."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 6000, 4, 50, 700
+    q, K, V = rand_case(9, P, Hq, Hkv, d, L, BF16)
+    q[:] = 0
+    out = gu.gpu_select(BF16, q, K, V, S, W, k)
+    want = list(range(S + k)) + list(range(L - W, L))
+    for c in range(Hkv):
+        assert out["kept"][0, c].tolist() == want
+    select_parity(ref, BF16, q, K, V, S, W, k)
+
+
+def test_select_duplicate_keys_straddling_the_threshold(ref):
+    """Copies of the k-th best key have exactly its score; only the lowest indices may be kept."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 4, 1, 128, 3000, 4, 20, 200
+    q, K, V = rand_case(10, P, Hq, Hkv, d, L, BF16)
+    s = ref.scores(BF16, GROUP_SUM, q, K)[0, 0, 0]
+    order = sorted(range(S, L - W), key=lambda i: (-float(s[i]), i))
+    kth = order[k - 1]
+    for j in (S, 1000, 1001, 2500, L - W - 1):  # plant copies, incl. first and last candidate
+        if j != kth:
+            K[0, 0, j] = K[0, 0, kth]
+    select_parity(ref, BF16, q, K, V, S, W, k)
+
+
+def test_select_strided_token_major_layout(ref):
+    """K, V stored [P, L, Hkv, d] (token-major) and passed through the stride fields."""
+    import torch
+
+    P, Hq, Hkv, d, L, S, W, k = 2, 8, 2, 128, 2000, 4, 32, 150
+    q, K, V = rand_case(11, P, Hq, Hkv, d, L, BF16)
+    Kd = synth.host_to_torch(np.ascontiguousarray(K.transpose(0, 2, 1, 3)), BF16).permute(0, 2, 1, 3)
+    Vd = synth.host_to_torch(np.ascontiguousarray(V.transpose(0, 2, 1, 3)), BF16).permute(0, 2, 1, 3)
+    assert not Kd.is_contiguous()
+    out = gu.gpu_select(BF16, q, None, None, S, W, k, K_dev=Kd, V_dev=Vd)
+    Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    assert gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k) == 0
+    np.testing.assert_array_equal(out["Kc"], Kc)
+    np.testing.assert_array_equal(out["Vc"], Vc)
+
+
+def test_select_is_deterministic():
+    q, K, V = rand_case(12, 2, 8, 2, 128, 20000, BF16)
+    first = gu.gpu_select(BF16, q, K, V, 4, 128, 1000)
+    for _ in range(4):
+        again = gu.gpu_select(BF16, q, K, V, 4, 128, 1000)
+        for name in ("kept", "Kc", "Vc", "scores"):
+            np.testing.assert_array_equal(first[name], again[name])
+
+
+def test_select_without_scores_out_matches(ref):
+    q, K, V = rand_case(13, 1, 8, 2, 128, 4099, BF16)
+    a = gu.gpu_select(BF16, q, K, V, 4, 64, 256, want_scores=True)
+    b = gu.gpu_select(BF16, q, K, V, 4, 64, 256, want_scores=False)
+    np.testing.assert_array_equal(a["kept"], b["kept"])
+    np.testing.assert_array_equal(a["Kc"], b["Kc"])
+
+
+def test_select_C2_shape_two_layers(ref):
+    """Config C2's row shape (32q/8kv, d128, bf16, L 32768, 4+1788+256) on 2 of its 32 layers."""
+    cfg = synth.CONFIGS["C2"].with_(n_layers=2)
+    q, K, V, pos = synth.kv_host(cfg)
+    out, _ = select_parity(ref, cfg.dtype, q, K, V, cfg.n_sink, cfg.n_recent, cfg.k)
+    kept = out["kept"].reshape(cfg.rows, -1)
+    for r in range(cfg.rows):
+        assert set(pos[r].tolist()) <= set(kept[r].tolist())
+
+
+# ----------------------------------------------------------------------------- error paths (host checks only)
+def test_invalid_arguments_are_rejected_before_launch():
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    q = torch.zeros((1, 4, 128), dtype=torch.bfloat16, device="cuda")
+    K = torch.zeros((1, 2, 512, 128), dtype=torch.bfloat16, device="cuda")
+    kept = torch.full((1, 2, 100), -7, dtype=torch.int32, device="cuda")
+    Kc = torch.zeros((1, 2, 100, 128), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+
+    def call(desc, ws_=ws):
+        sk.sagekv_select(desc, q, K, K, Kc, Kc, kept, None, ws_)
+
+    good = sk.select_desc(q, K, K, 4, 32, 64, 100)
+    call(good)
+    for field, value, code in [("k", 600, 1), ("n_recent", 0, 1), ("compact_capacity", 50, 1), ("n_q_heads", 3, 1),
+                               ("head_dim", 96, 2), ("dtype", 5, 2), ("head_mode", 1, 2), ("k_stride_token", 100, 2)]:
+        bad = sk.select_desc(q, K, K, 4, 32, 64, 100)
+        setattr(bad, field, value)
+        kept.fill_(-7)
+        with pytest.raises(sk.SagekvError) as e:
+            call(bad)
+        assert e.value.code == code, field
+        assert sk.sagekv_select_workspace_bytes(bad) == 0
+        torch.cuda.synchronize()
+        assert int(kept.max()) == -7  # nothing written
+    with pytest.raises(sk.SagekvError) as e:
+        call(good, ws[:1024])
+    assert e.value.code == 3
+
+
+# ----------------------------------------------------------------------------- decode
+def decode_case(ref, dtype, P, Hq, Hkv, d, S, k, W, steps, seed, grow=False, fused=True):
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    Bt = S + k + W
+    cap = Bt + (steps if grow else 3)
+    key = synth.stream_key(seed, 66)
+    Kc = synth.fill_host(key, 0, P * Hkv * cap * d, dtype).reshape(P, Hkv, cap, d)
+    Vc = synth.fill_host(key, 1 << 30, P * Hkv * cap * d, dtype).reshape(P, Hkv, cap, d)
+    Kc_d, Vc_d = synth.host_to_torch(Kc, dtype), synth.host_to_torch(Vc, dtype)
+    desc, ws, out = gu.gpu_decode_setup(dtype, P, Hq, Hkv, d, S, k, W, cap, grow)
+    length = Bt
+    worst = 0.0
+    for t in range(steps):
+        q = synth.fill_host(key, (2 << 30) + t * 10_000_000, P * Hq * d, dtype).reshape(P, Hq, d)
+        kn = synth.fill_host(key, (3 << 30) + t * 10_000_000, P * Hkv * d, dtype).reshape(P, Hkv, d)
+        vn = synth.fill_host(key, (4 << 30) + t * 10_000_000, P * Hkv * d, dtype).reshape(P, Hkv, d)
+        length = ref.append(dtype, Kc, Vc, kn, vn, S + k, W, grow=grow, length=length)
+        want = ref.decode_attn(dtype, GROUP_SUM, q, Kc, Vc, length)
+        qd, knd, vnd = (synth.host_to_torch(x, dtype) for x in (q, kn, vn))
+        if fused:
+            sk.sagekv_decode_step(desc, qd, knd, vnd, Kc_d, Vc_d, t, out, ws)
+        else:
+            sk.sagekv_append(desc, knd, vnd, Kc_d, Vc_d, t)
+            sk.sagekv_decode_attn(desc, qd, Kc_d, Vc_d, length, out, ws)
+        torch.cuda.synchronize()
+        err = np.abs(out.cpu().numpy() - want).max()
+        worst = max(worst, float(err))
+        assert err <= gu.DECODE_ATOL[dtype], f"step {t}: abs err {err:.3e}"
+    # the physical cache holds the same multiset of rows as the oracle's shifted one
+    got_K = synth.torch_to_host(Kc_d, dtype)
+    np.testing.assert_array_equal(got_K[:, :, :S + k], Kc[:, :, :S + k])
+    if not grow:
+        for p in range(P):
+            for c in range(Hkv):
+                a = sorted(map(bytes, got_K[p, c, S + k:Bt]))
+                b = sorted(map(bytes, Kc[p, c, S + k:Bt]))
+                assert a == b
+    else:
+        np.testing.assert_array_equal(got_K[:, :, :length], Kc[:, :, :length])
+    return worst
+
+
+@pytest.mark.parametrize(
+    "dtype,Hq,Hkv,d,S,k,W,steps",
+    [
+        (F32, 4, 2, 64, 4, 188, 64, 8),      # config C1's decode shape
+        (BF16, 8, 2, 128, 4, 300, 33, 40),   # window wraps around (steps > W)
+        (BF16, 7, 1, 128, 4, 500, 64, 5),    # G=7
+        (BF16, 4, 4, 64, 0, 90, 5, 7),       # G=1, d=64, no sink
+        (F32, 6, 2, 128, 2, 100, 9, 12),     # fp32 d=128
+        (BF16, 20, 2, 128, 4, 200, 16, 3),   # G=10: two launches per step
+    ],
+)
+def test_decode_steps_fused(ref, dtype, Hq, Hkv, d, S, k, W, steps):
+    decode_case(ref, dtype, 2, Hq, Hkv, d, S, k, W, steps, seed=20 + Hq)
+
+
+def test_decode_steps_separate_append(ref):
+    decode_case(ref, BF16, 2, 8, 2, 128, 4, 300, 33, 6, seed=31, fused=False)
+
+
+def test_decode_grow_mode(ref):
+    decode_case(ref, BF16, 1, 8, 2, 128, 4, 100, 16, 6, seed=32, grow=True)
+    decode_case(ref, F32, 1, 4, 2, 64, 4, 100, 16, 4, seed=33, grow=True, fused=False)
+
+
+def test_decode_len_one_and_long_rows(ref):
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    P, Hq, Hkv, d, cap = 3, 8, 2, 128, 9000
+    key = synth.stream_key(40, 66)
+    Kc = synth.fill_host(key, 0, P * Hkv * cap * d, BF16).reshape(P, Hkv, cap, d)
+    Vc = synth.fill_host(key, 1 << 30, P * Hkv * cap * d, BF16).reshape(P, Hkv, cap, d)
+    q = synth.fill_host(key, 2 << 30, P * Hq * d, BF16).reshape(P, Hq, d)
+    desc, ws, out = gu.gpu_decode_setup(BF16, P, Hq, Hkv, d, 4, cap - 4 - 8, 8, cap)
+    Kd, Vd, qd = (synth.host_to_torch(x, BF16) for x in (Kc, Vc, q))
+    for length in (1, 2, 63, 64, 65, 4097, cap):
+        sk.sagekv_decode_attn(desc, qd, Kd, Vd, length, out, ws)
+        torch.cuda.synchronize()
+        want = ref.decode_attn(BF16, GROUP_SUM, q, Kc, Vc, length)
+        assert np.abs(out.cpu().numpy() - want).max() <= gu.DECODE_ATOL[BF16], length
+    sk.sagekv_decode_attn(desc, qd, Kd, Vd, 1, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for h in range(Hq):  # one entry: the output is that value row, exactly
+        np.testing.assert_array_equal(got[:, h], synth.to_f64(Vc[:, h // 4, 0], BF16).astype(np.float32))
+
+
+def test_nothing_evicted_equals_full_attention_end_to_end(ref):
+    """k = E: select then decode over the reduced cache equals plain attention over the full cache."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    P, Hq, Hkv, d, L, S, W = 1, 8, 2, 128, 3000, 4, 40
+    q, K, V = rand_case(50, P, Hq, Hkv, d, L, BF16)
+    out = gu.gpu_select(BF16, q, K, V, S, W, L - S - W)
+    desc, ws, o = gu.gpu_decode_setup(BF16, P, Hq, Hkv, d, S, L - S - W, W, L)
+    qd = synth.host_to_torch(q, BF16)
+    sk.sagekv_decode_attn(desc, qd, out["Kc_dev"], out["Vc_dev"], L, o, ws)
+    torch.cuda.synchronize()
+    got = o.cpu().numpy()
+    for c in range(Hkv):
+        full = ref.full_attention(BF16, np.ascontiguousarray(q[0, 4 * c:4 * c + 4]), K[0, c], V[0, c])
+        assert np.abs(got[0, 4 * c:4 * c + 4] - full).max() <= gu.DECODE_ATOL[BF16]
+
+
+def test_C1_end_to_end(ref):
+    """Config C1: select, then 8 decode steps with the config's seeded q / k_new / v_new."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    cfg = synth.CONFIGS["C1"]
+    q, K, V, _ = synth.kv_host(cfg)
+    S, W, k = cfg.n_sink, cfg.n_recent, cfg.k
+    out = gu.gpu_select(cfg.dtype, q, K, V, S, W, k)
+    Kc, Vc, kept = ref.select(cfg.dtype, GROUP_SUM, q, K, V, S, W, k)
+    np.testing.assert_array_equal(out["kept"], kept)
+    desc, ws, o = gu.gpu_decode_setup(cfg.dtype, cfg.n_problems, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, S, k, W,
+                                      cfg.budget)
+    for t in range(cfg.decode_steps):
+        qs, kn, vn = synth.decode_inputs_host(cfg, t)
+        ref.append(cfg.dtype, Kc, Vc, kn, vn, S + k, W)
+        want = ref.decode_attn(cfg.dtype, GROUP_SUM, qs, Kc, Vc, cfg.budget)
+        qd, knd, vnd = (synth.host_to_torch(x, cfg.dtype) for x in (qs, kn, vn))
+        sk.sagekv_decode_step(desc, qd, knd, vnd, out["Kc_dev"], out["Vc_dev"], t, o, ws)
+        torch.cuda.synchronize()
+        assert np.abs(o.cpu().numpy() - want).max() <= gu.DECODE_ATOL[cfg.dtype]
