@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the SAGE-KV hot path on one MI355X.
+
+One "step" = the whole path over one synthetic batch: the eviction pass (score, softmax, GQA
+combine, top-k, gather) over every layer and KV head of the cache, followed by the config's
+decode steps (append + attention over the reduced cache, all layers per step).  Inputs are
+seeded, generated on the device and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is the algorithmic bytes of a step (K once + survivors of K and V
+read and written + indices, plus the reduced K and V once per decode step) divided by the step
+time; the two halves of the metric (select GB/s, decode tokens/s) and their fractions of the
+8 TB/s HBM peak are reported beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(cfg):
+    """(select bytes per pass, decode bytes per decode step, score-kernel bytes per launch)."""
+    e, d = cfg.elem_bytes, cfg.head_dim
+    per_row = cfg.L * d * e + 4 * cfg.budget * d * e + 4 * cfg.budget
+    select = cfg.rows * per_row
+    decode = 2 * cfg.rows * cfg.budget * d * e
+    score = cfg.rows * cfg.L * d * e
+    return select, decode, score
+
+
+def read_traffic(cfg_name):
+    """HBM bytes per score-kernel launch from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"score_kernel_{cfg_name}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(cfg, n_layers, n_decode):
+    """Times the CPU oracle, as it stands, on the first n_layers layers of the same workload."""
+    import numpy as np
+
+    import synth
+    from oracle import ref
+
+    sub = cfg.with_(n_layers=n_layers)
+    q = synth.q_last_host(cfg)[: sub.n_problems].copy()
+    pos, nrows = synth.needles(sub, q)
+    shp = (sub.n_problems, sub.n_kv_heads, sub.L, sub.head_dim)
+    K = np.stack([synth.kv_row_host(sub, "K", r, pos, nrows) for r in range(sub.rows)]).reshape(shp)
+    V = np.stack([synth.kv_row_host(sub, "V", r) for r in range(sub.rows)]).reshape(shp)
+    t0 = time.perf_counter()
+    Kc, Vc, kept = ref.select(sub.dtype, ref.GROUP_SUM, q, K, V, sub.n_sink, sub.n_recent, sub.k)
+    t_sel = time.perf_counter() - t0
+    t_dec = 0.0
+    P, d = cfg.n_problems, cfg.head_dim
+    for t in range(n_decode):
+        qs, kn, vn = synth.decode_inputs_host(cfg, t)
+        qs, kn, vn = (np.ascontiguousarray(x[: sub.n_problems]) for x in (qs, kn, vn))
+        t0 = time.perf_counter()
+        ref.append(sub.dtype, Kc, Vc, kn, vn, sub.n_sink + sub.k, sub.n_recent)
+        ref.decode_attn(sub.dtype, ref.GROUP_SUM, qs, Kc, Vc, sub.budget)
+        t_dec += time.perf_counter() - t0
+    sel_b, dec_b, _ = algorithmic_bytes(sub)
+    total_b = sel_b + n_decode * dec_b
+    return {
+        "value": total_b / (t_sel + t_dec) / 1e9,
+        "unit": "GB/s",
+        "cores": ref.threads(),
+        "kind": "oracle",
+        "sample": f"first {n_layers} of {cfg.n_layers} layers ({sub.rows} rows of L={cfg.L}): 1 eviction pass + "
+                  f"{n_decode} decode steps",
+        "select_GBps": sel_b / t_sel / 1e9,
+        "select_s": t_sel,
+        "decode_tokens_per_s": (n_decode * cfg.batch / t_dec) * (n_layers / cfg.n_layers) if t_dec > 0 else None,
+        "decode_s": t_dec,
+    }, kept
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="C3", help="C2, C3 (default: the 128K Llama-3.1-8B-shaped target), C4, C5")
+    ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per step (default: the config's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--cpu-decode-steps", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (rows are independent; no collectives are built). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_08879_amd as sk
+    import synth
+
+    cfg = synth.CONFIGS[args.config]
+    n_dec = cfg.decode_steps if args.decode_steps is None else args.decode_steps
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    S, W, k, Bt = cfg.n_sink, cfg.n_recent, cfg.k, cfg.budget
+
+    # ---- inputs, resident in HBM
+    q_last, K, V, _ = synth.kv_device(cfg, dev)
+    td = synth.torch_dtype(cfg.dtype)
+    P, Hq, Hkv, d = cfg.n_problems, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    q_steps = torch.empty((max(n_dec, 1), P, Hq, d), dtype=td, device=dev)
+    kn_steps = torch.empty((max(n_dec, 1), P, Hkv, d), dtype=td, device=dev)
+    vn_steps = torch.empty((max(n_dec, 1), P, Hkv, d), dtype=td, device=dev)
+    synth.fill_device(q_steps, synth.stream_key(cfg.seed, synth.T_QSTEP))
+    synth.fill_device(kn_steps, synth.stream_key(cfg.seed, synth.T_KNEW))
+    synth.fill_device(vn_steps, synth.stream_key(cfg.seed, synth.T_VNEW))
+
+    # ---- outputs and workspaces (allocated once, outside the timed region)
+    sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt)
+    sws = torch.empty(sk.sagekv_select_workspace_bytes(sdesc), dtype=torch.uint8, device=dev)
+    Kc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
+    Vc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
+    kept = torch.zeros((P, Hkv, Bt), dtype=torch.int32, device=dev)
+    ddesc = sk.decode_desc(P, Hq, Hkv, d, cfg.dtype, S, k, W, Bt)
+    dws = torch.empty(sk.sagekv_decode_workspace_bytes(ddesc), dtype=torch.uint8, device=dev)
+    out = torch.empty((P, Hq, d), dtype=torch.float32, device=dev)
+
+    def one_step(ev=None):
+        if ev:
+            ev[0].record()
+        sk.sagekv_select(sdesc, q_last, K, V, Kc, Vc, kept, None, sws)
+        if ev:
+            ev[1].record()
+        for t in range(n_dec):
+            sk.sagekv_decode_step(ddesc, q_steps[t], kn_steps[t], vn_steps[t], Kc, Vc, t, out, dws)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    sk.sagekv_stage_timing_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    stage_ms = np.array([sk.sagekv_stage_timing_read(0, i) for i in range(args.steps)]).mean(axis=0)
+    n_dec_timed = min(args.steps, max(n_dec * args.steps, 0))
+    dec_kernel_ms = float(np.mean([sk.sagekv_stage_timing_read(1, i)[0] for i in range(n_dec_timed)])) if n_dec else None
+    sk.sagekv_stage_timing_enable(0)
+
+    sel_b, dec_b, score_b = algorithmic_bytes(cfg)
+    ms_per_step = elapsed / args.steps * 1e3
+    total_b = sel_b + n_dec * dec_b
+    value = total_b / (ms_per_step * 1e-3) / 1e9
+    sel_gbps = sel_b / (sel_ms * 1e-3) / 1e9
+    dec_tok_s = (n_dec * cfg.batch) / (dec_ms * 1e-3) if n_dec else None
+    dec_gbps = (n_dec * dec_b) / (dec_ms * 1e-3) / 1e9 if n_dec else None
+    score_ms = float(stage_ms[0])
+    score_gbps = score_b / (score_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "select pass GB/s + compressed decode-attn tokens/s, % of HBM roofline",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == synth.BF16 else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: {cfg.n_layers} layers x batch {cfg.batch}, {Hq}q/{Hkv}kv heads, head_dim {d}, "
+                        f"L={cfg.L}, budget {Bt} = {S} sink + {k} top-k + {W} recent, {n_dec} decode steps per step",
+            "rows": cfg.rows,
+            "step": "1 eviction pass over the whole cache + the decode steps",
+        },
+        "frac_hbm": round(value / HBM_PEAK_GBPS, 4),
+        "select": {"ms": round(sel_ms, 4), "GBps": round(sel_gbps, 1), "frac_hbm": round(sel_gbps / HBM_PEAK_GBPS, 4),
+                   "algorithmic_bytes": sel_b,
+                   "stage_ms": {n: round(float(v), 4) for n, v in zip(sk.binding.STAGES, stage_ms)}},
+        "decode": {"tokens_per_s": None if dec_tok_s is None else round(dec_tok_s, 1),
+                   "ms_per_token": None if not n_dec else round(dec_ms / n_dec, 5),
+                   "GBps": None if dec_gbps is None else round(dec_gbps, 1),
+                   "frac_hbm": None if dec_gbps is None else round(dec_gbps / HBM_PEAK_GBPS, 4),
+                   "kernel_ms": None if dec_kernel_ms is None else round(dec_kernel_ms, 5),
+                   "algorithmic_bytes_per_token": dec_b},
+        "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(score_ms, 4),
+                     "algorithmic_bytes": score_b, "traffic": read_traffic(cfg.name)},
+    }
+    if not args.no_cpu_baseline:
+        base, kept_ref = cpu_baseline(cfg, args.cpu_layers, args.cpu_decode_steps)
+        # free check: the sampled layers' kept sets must be the oracle's
+        sk.sagekv_select(sdesc, q_last, K, V, Kc, Vc, kept, None, sws)
+        torch.cuda.synchronize()
+        got = kept[: kept_ref.shape[0]].cpu().numpy()
+        base["kept_sets_equal_oracle_rows"] = int((got == kept_ref).all(axis=-1).sum())
+        base["rows_checked"] = int(kept_ref.shape[0] * kept_ref.shape[1])
+        result["cpu_baseline"] = base
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -112,12 +112,9 @@ typedef struct {
 sagekv_status sagekv_append(const sagekv_decode_desc* desc, const void* k_new, const void* v_new, void* Kc,
                             void* Vc, int32_t n_appended, void* hip_stream);
 
+/* Bytes of device scratch the decode calls need (may be 0: then `workspace` may be null).
+ * The scratch needs no initialisation and carries no state between calls. */
 size_t sagekv_decode_workspace_bytes(const sagekv_decode_desc* desc);
-
-/* Zero-fills a decode workspace.  Required once before its first use; every decode call
- * leaves the workspace ready for the next one. */
-sagekv_status sagekv_decode_workspace_init(const sagekv_decode_desc* desc, void* workspace,
-                                           size_t workspace_bytes, void* hip_stream);
 
 /* Step 4's attention: out[h] = sum_t softmax_t( q[h] . Kc[c][t] / sqrt(head_dim) ) Vc[c][t],
  * t in [0, len), c = h / G.   q [n_problems, Hq, head_dim]; out [n_problems, Hq, head_dim] fp32.

@@ -18,7 +18,7 @@ STAGES = ("score", "stats", "combine", "topk", "gather")
 
 EXPORTS = (
     "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_append",
-    "sagekv_decode_workspace_bytes", "sagekv_decode_workspace_init", "sagekv_decode_attn", "sagekv_decode_step",
+    "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read",
 )
 
@@ -71,8 +71,6 @@ def lib():
         L.sagekv_append.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, i32, vp]
         L.sagekv_decode_workspace_bytes.restype = sz
         L.sagekv_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
-        L.sagekv_decode_workspace_init.restype = ctypes.c_int
-        L.sagekv_decode_workspace_init.argtypes = [ctypes.POINTER(DecodeDesc), vp, sz, vp]
         L.sagekv_decode_attn.restype = ctypes.c_int
         L.sagekv_decode_attn.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step.restype = ctypes.c_int
@@ -150,11 +148,6 @@ def sagekv_decode_workspace_bytes(desc: DecodeDesc) -> int:
 
 def _ws_bytes(ws):
     return 0 if ws is None else ws.numel() * ws.element_size()
-
-
-def sagekv_decode_workspace_init(desc: DecodeDesc, workspace) -> None:
-    _check(lib().sagekv_decode_workspace_init(ctypes.byref(desc), _ptr(workspace), _ws_bytes(workspace), _stream()),
-           "sagekv_decode_workspace_init")
 
 
 def sagekv_append(desc: DecodeDesc, k_new, v_new, Kc, Vc, n_appended: int) -> None:

@@ -86,12 +86,15 @@ bool check_decode(const sagekv_decode_desc* d, sagekv_status* st) {
 }
 
 struct DecodeLayout {
-  size_t counters, part_ml, part_acc, total;
+  size_t part_ml, part_acc, total;
   int max_splits, rows, G;
 };
 
-// Splits per row: enough workgroups to fill 256 CUs several times over, at least 256 tokens each.
+// Splits per row.  With about one row per CU or more, a single 16-wave workgroup per row fills
+// the chip and needs no merge launch; otherwise enough workgroups to fill 256 CUs several times
+// over, at least 256 tokens each.
 int splits_for(int rows, int len) {
+  if (rows >= 192) return 1;
   int want = (2048 + rows - 1) / rows;
   int most = (len + 255) / 256;
   int n = want < most ? want : most;
@@ -104,13 +107,11 @@ DecodeLayout decode_layout(const sagekv_decode_desc* d) {
   l.G = d->n_q_heads / d->n_kv_heads;
   l.max_splits = splits_for(l.rows, d->compact_capacity);
   size_t off = 0;
-  l.counters = off;
-  off = align_up(off + (size_t)l.rows * sizeof(int));
   l.part_ml = off;
   off = align_up(off + (size_t)l.rows * l.max_splits * l.G * sizeof(float2));
   l.part_acc = off;
   off = align_up(off + (size_t)l.rows * l.max_splits * l.G * d->head_dim * sizeof(float));
-  l.total = off;
+  l.total = l.max_splits > 1 ? off : 0;  // one split per row writes `out` directly
   return l;
 }
 
@@ -145,7 +146,7 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
                          void* Kc, void* Vc, int slot, int len, float* out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
   const DecodeLayout l = decode_layout(d);
-  if (!ws || ws_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
+  if (l.total > 0 && (!ws || ws_bytes < l.total)) return SAGEKV_ERR_WORKSPACE;
   DecodeParams p;
   p.n_problems = d->n_problems;
   p.Hq = d->n_q_heads;
@@ -165,7 +166,6 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
   if (p.n_splits > l.max_splits) p.n_splits = l.max_splits;
   const int tps = (len + p.n_splits - 1) / p.n_splits;
   p.tokens_per_split = (tps + 63) / 64 * 64;
-  p.counters = (int*)((char*)ws + l.counters);
   p.part_ml = (float2*)((char*)ws + l.part_ml);
   p.part_acc = (float*)((char*)ws + l.part_acc);
   p.out = out;
@@ -339,15 +339,6 @@ size_t sagekv_decode_workspace_bytes(const sagekv_decode_desc* desc) {
   sagekv_status st;
   if (!check_decode(desc, &st)) return 0;
   return decode_layout(desc).total;
-}
-
-sagekv_status sagekv_decode_workspace_init(const sagekv_decode_desc* desc, void* workspace, size_t workspace_bytes,
-                                           void* hip_stream) {
-  sagekv_status st;
-  if (!check_decode(desc, &st)) return st;
-  const DecodeLayout l = decode_layout(desc);
-  if (!workspace || workspace_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
-  return dev(launch_fill_zero(workspace, l.part_ml, (hipStream_t)hip_stream));
 }
 
 sagekv_status sagekv_decode_attn(const sagekv_decode_desc* d, const void* q, const void* Kc, const void* Vc,

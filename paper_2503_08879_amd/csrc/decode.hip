@@ -3,10 +3,14 @@
 //
 // decode_kernel: grid (splits, rows).  A workgroup streams its slice of Kc and Vc once for all
 // G heads of the row (16-byte loads, LPT lanes per token), keeps an online softmax per lane
-// group, merges lane groups -> waves -> workgroup, writes a partial (max, sum, acc[G][d]); the
-// last workgroup of a row to finish (atomic ticket) merges the splits into out.  The appended
-// token is read from k_new / v_new directly and stored to its slot by the workgroup that owns
-// it, so append and attention are one launch.
+// group and merges lane groups -> waves -> workgroup.  With one split per row (many rows: all
+// layers of a step in one launch) a 16-wave workgroup owns the whole row and writes `out`
+// itself; with few rows the row is split, partials (max, sum, acc[G][d]) go to scratch and
+// combine_kernel merges them.  (A last-workgroup-done merge inside one kernel needs a device
+// scope fence in every workgroup, which on this multi-XCD part writes back and invalidates
+// L2: measured ~8x slower than two launches.)  The appended token is read from k_new / v_new
+// directly and stored to its slot by the workgroup that owns it, so append and attention are
+// one launch.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -14,21 +18,18 @@ namespace sagekv {
 
 namespace {
 
-constexpr int kDecThreads = 256;
-constexpr int kDecWaves = kDecThreads / kWave;
-
-template <int DT, int D, int GB>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p, int g0) {
+template <int DT, int D, int GB, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0) {
   constexpr int EPL = Elem<DT>::per_lane;
   constexpr int EB = Elem<DT>::bytes;
   constexpr int LPT = D / EPL;
   constexpr int TPL = 64 / LPT;
-  constexpr int SB = GB > 4 ? 4 : 8;  // loads per batch
+  constexpr int SB = (GB > 4 || NW > 4) ? 4 : 8;  // loads per batch
   constexpr int ROWB = D * EB;
+  constexpr int kDecWaves = NW, kDecThreads = NW * 64;
 
   __shared__ float s_acc[kDecWaves][GB][D];
   __shared__ float2 s_ml[kDecWaves][GB];
-  __shared__ int s_last;
 
   const int row = blockIdx.y, split = blockIdx.x;
   const int prob = row / p.Hkv, c = row % p.Hkv;
@@ -140,7 +141,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p, int
   }
   __syncthreads();
 
-  // merge the waves, write this split's partial
+  // merge the waves; one split: finish here, else write this split's partial
+  const bool single = p.n_splits == 1;
   float* pa = p.part_acc + (((int64_t)row * p.n_splits + split) * p.G + g0) * D;
   float2* pml = p.part_ml + ((int64_t)row * p.n_splits + split) * p.G + g0;
   for (int it = tid; it < GB * D; it += kDecThreads) {
@@ -156,34 +158,35 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p, int
       a += s_acc[w][g][j] * f;
       ls += ml.y * f;
     }
-    pa[(int64_t)g * D + j] = a;
-    if (j == 0) pml[g] = make_float2(M, ls);
+    if (single) {
+      p.out[((int64_t)prob * p.Hq + c * p.G + g0 + g) * D + j] = a / ls;
+    } else {
+      pa[(int64_t)g * D + j] = a;
+      if (j == 0) pml[g] = make_float2(M, ls);
+    }
   }
+}
 
-  // last workgroup of the row merges the splits
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) s_last = (atomicAdd(&p.counters[row], 1) == p.n_splits - 1);
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  for (int it = tid; it < GB * D; it += kDecThreads) {
+// Merges the splits of a row: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
+__global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int prob = row / p.Hkv, c = row % p.Hkv;
+  const int D = p.D;
+  for (int it = tid; it < p.G * D; it += 256) {
     const int g = it / D, j = it % D;
-    const float2* ml = p.part_ml + (int64_t)row * p.n_splits * p.G + g0 + g;
-    const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g0 + g) * D + j;
+    const float2* ml = p.part_ml + (int64_t)row * p.n_splits * p.G + g;
+    const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g) * D + j;
     float M = -INFINITY;
-    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, __builtin_nontemporal_load(&ml[(int64_t)s * p.G].x));
+    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, ml[(int64_t)s * p.G].x);
     float num = 0.f, den = 0.f;
     for (int s = 0; s < p.n_splits; ++s) {
-      const float ms = __builtin_nontemporal_load(&ml[(int64_t)s * p.G].x);
-      const float ls = __builtin_nontemporal_load(&ml[(int64_t)s * p.G].y);
-      const float f = (ms == -INFINITY) ? 0.f : exp_fast(ms - M);
-      num += __builtin_nontemporal_load(&a[(int64_t)s * p.G * D]) * f;
-      den += ls * f;
+      const float2 v = ml[(int64_t)s * p.G];
+      const float f = (v.x == -INFINITY) ? 0.f : exp_fast(v.x - M);
+      num += a[(int64_t)s * p.G * D] * f;
+      den += v.y * f;
     }
-    p.out[((int64_t)prob * p.Hq + c * p.G + g0 + g) * D + j] = num / den;
+    p.out[((int64_t)prob * p.Hq + c * p.G + g) * D + j] = num / den;
   }
-  if (tid == 0) p.counters[row] = 0;  // ready for the next launch
 }
 
 template <int LPT>
@@ -202,10 +205,16 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* p, size_t n) {
 
 template <int DT, int D>
 hipError_t launch_decode_g(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
+  const bool single = p.n_splits == 1;  // one workgroup per row: use a big one
   switch (gb) {
-#define SAGEKV_CASE(N) \
-  case N:              \
-    hipLaunchKernelGGL((decode_kernel<DT, D, N>), grid, dim3(kDecThreads), 0, s, p, g0); \
+#define SAGEKV_CASE(N)                                                                               \
+  case N:                                                                                            \
+    if (!single)                                                                                     \
+      hipLaunchKernelGGL((decode_kernel<DT, D, N, 4>), grid, dim3(256), 0, s, p, g0);                \
+    else if (N <= 4)                                                                                 \
+      hipLaunchKernelGGL((decode_kernel<DT, D, N, 16>), grid, dim3(1024), 0, s, p, g0);              \
+    else                                                                                             \
+      hipLaunchKernelGGL((decode_kernel<DT, D, N, 8>), grid, dim3(512), 0, s, p, g0);                \
     break;
     SAGEKV_CASE(1) SAGEKV_CASE(2) SAGEKV_CASE(3) SAGEKV_CASE(4)
     SAGEKV_CASE(5) SAGEKV_CASE(6) SAGEKV_CASE(7) SAGEKV_CASE(8)
@@ -231,6 +240,10 @@ hipError_t launch_decode(const DecodeParams& p, hipStream_t s) {
     else
       e = p.D == 128 ? launch_decode_g<DT_F32, 128>(q, g0, gb, grid, s) : launch_decode_g<DT_F32, 64>(q, g0, gb, grid, s);
     if (e != hipSuccess) return e;
+  }
+  if (p.n_splits > 1) {
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)rows), dim3(256), 0, s, p);
+    return hipGetLastError();
   }
   return hipSuccess;
 }

@@ -90,7 +90,6 @@ struct DecodeParams {
   int n_splits, tokens_per_split;
   float* part_acc;     // [rows][n_splits][G][D]
   float2* part_ml;     // [rows][n_splits][G]   (max, sum)
-  int* counters;       // [rows], zero between launches
   float* out;          // [P][Hq][D]
   float scale;
 };

@@ -34,6 +34,10 @@ struct TopkShared {
 // Largest digit b such that count(digits >= b) >= k_rem; returns b and the rank left inside it.
 __device__ void pick_digit(TopkShared& sh, int nb, int k_rem, int* bin, int* rem) {
   const int t = threadIdx.x;
+  if (t == 0) {
+    sh.pick_bin = 0;
+    sh.pick_rem = 1;
+  }
   const int i0 = nb - 1 - 2 * t, i1 = nb - 2 - 2 * t;  // descending digits
   const int c0 = i0 >= 0 ? sh.hist[i0] : 0;
   const int c1 = i1 >= 0 ? sh.hist[i1] : 0;
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
         const bool gt = key[j] > tau, eq = key[j] == tau;
         if (gt || (eq && eq_before < quota)) {
           const int pos = gt_before + (eq_before < quota ? eq_before : quota);
-          kept[S + pos] = (int32_t)(S + i0 + j);
+          if (pos < k) kept[S + pos] = (int32_t)(S + i0 + j);
         }
         gt_before += gt;
         eq_before += eq;
@@ -199,7 +203,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
   for (int it = 0; it < kGatherTokens / TPI; ++it) {
     const int t = t0 + it * TPI + sub;
     if (t < p.n_kept) {
-      const int64_t src = kept[t];
+      int64_t src = kept[t];
+      src = src < 0 ? 0 : (src >= p.geo.L ? p.geo.L - 1 : src);  // never read outside the row
       const uint4 a = ld16(Kr + src * p.ks_token * eb + cl * 16);
       const uint4 b = ld16(Vr + src * p.vs_token * eb + cl * 16);
       st16(Kc + t * row_bytes + cl * 16, a);

@@ -95,6 +95,5 @@ def gpu_decode_setup(dtype, P, Hq, Hkv, d, S, k, W, cap, grow=False):
 
     desc = sk.decode_desc(P, Hq, Hkv, d, dtype, S, k, W, cap, grow)
     ws = torch.empty(max(sk.sagekv_decode_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
-    sk.sagekv_decode_workspace_init(desc, ws)
     out = torch.empty((P, Hq, d), dtype=torch.float32, device="cuda")
     return desc, ws, out

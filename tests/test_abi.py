@@ -16,7 +16,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert "sagekv_select" in names and "sagekv_decode_attn" in names and len(names) >= 10
+    assert "sagekv_select" in names and "sagekv_decode_attn" in names and len(names) == 9
     lib = ctypes.CDLL(sk.binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -36,7 +36,7 @@ def test_status_strings_and_host_side_checks():
     # null pointers are rejected on the host, before any launch (safe without a GPU)
     code = sk.binding.lib().sagekv_select(ctypes.byref(good), None, None, None, None, None, None, None, None, 0, None)
     assert code == 1
-    dd = sk.decode_desc(32, 32, 8, 128, 0, 4, 3580, 512, 4096)
+    dd = sk.decode_desc(1, 32, 8, 128, 0, 4, 3580, 512, 4096)  # few rows: split rows need scratch
     assert sk.sagekv_decode_workspace_bytes(dd) > 0
     assert sk.binding.lib().sagekv_decode_attn(ctypes.byref(dd), None, None, None, 10, None, None, 0, None) == 1
     dd.compact_capacity = 100
