@@ -57,7 +57,7 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   l.n_chunks = (int)((d->L + kScoreChunk - 1) / kScoreChunk);
   size_t off = 0;
   l.logits = off;
-  off = align_up(off + (size_t)l.rows * l.G * l.Lp * sizeof(float));
+  off = align_up(off + (size_t)l.rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
   l.scores = off;
   if (own_scores) off = align_up(off + (size_t)l.rows * l.Lp * sizeof(float));
   l.partials = off;
@@ -260,6 +260,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   CombineParams cp;
   cp.geo = geo;
   cp.logits = logits;
+  cp.n_chunks = l.n_chunks;
   cp.stats = stats;
   cp.scores = scores;
   cp.pitch = pitch;

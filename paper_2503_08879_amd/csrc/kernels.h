@@ -29,7 +29,7 @@ struct ScoreParams {
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;  // elements
-  float* logits;                          // [rows][G][Lp]
+  float* logits;                          // [rows][n_chunks][G][kScoreChunk]
   float2* partials;                       // [rows][G][n_chunks]  (max, sum exp(x - max))
   int n_chunks;
   int g0;  // first head of the group handled by this launch
@@ -46,6 +46,7 @@ struct StatsParams {
 struct CombineParams {
   RowGeom geo;
   const float* logits;
+  int n_chunks;  // score chunks per row (logit scratch layout)
   const RowStat* stats;
   float* scores;  // [rows][pitch]
   int64_t pitch;

@@ -17,6 +17,13 @@ constexpr int kScoreThreads = 256;
 constexpr int kScoreWaves = kScoreThreads / kWave;
 constexpr int kBlocksPerWave = kScoreChunk / (kScoreWaves * 64);  // 64-token blocks per wave
 
+// Logit scratch layout: [row][chunk][head][kScoreChunk], so a score workgroup writes one
+// contiguous block and the combine stage still reads 16 bytes per head per thread.
+__device__ __forceinline__ int64_t logit_index(const RowGeom& geo, int n_chunks, int row, int g, int64_t tok) {
+  const int64_t chunk = tok / kScoreChunk;
+  return (((int64_t)row * n_chunks + chunk) * geo.G + g) * kScoreChunk + (tok - chunk * kScoreChunk);
+}
+
 // One wave handles 64 tokens per block: LPT lanes share a token (16 bytes each), so one
 // 16-byte load instruction covers TPL = 64/LPT whole tokens, fully coalesced; LPT such loads
 // make a block.  After load i the lane with (lane % LPT) == i keeps the reduced dot product,
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
         float x = keep[g] * p.scale;
-        p.logits[((int64_t)row * p.geo.G + p.g0 + g) * p.geo.Lp + tok] = x;
+        p.logits[logit_index(p.geo, p.n_chunks, row, p.g0 + g, tok)] = x;
         float mn = fmaxf(m[g], x);
         sum[g] = sum[g] * exp_fast(m[g] - mn) + exp_fast(x - mn);
         m[g] = mn;
@@ -111,6 +118,165 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
       float2 pw = part[w][g];
       s += (pw.x == -INFINITY) ? 0.f : pw.y * exp_fast(pw.x - M);
     }
+    p.partials[((int64_t)row * p.geo.G + p.g0 + g) * p.n_chunks + blockIdx.x] = make_float2(M, s);
+  }
+}
+
+// bf16 scoring on the matrix cores.  The dot products of a 16-token tile against the group's
+// query heads are one 16x16x(head_dim) product: A = queries (heads in rows, zero padded),
+// B = keys (tokens in columns), fp32 accumulate.  MFMA operands want a lane to hold 8
+// consecutive elements of ONE token per column lane, while coalesced loads give adjacent lanes
+// adjacent 16-byte chunks of the SAME token, so each wave stages its 64-token block through a
+// private, XOR-swizzled LDS buffer (conflict free both ways).  GPAD = heads padded to 4, 8 or
+// 16: 16/GPAD tiles share an accumulator (the queries of tile t sit in rows t*GPAD..), so after
+// a block every lane owns 4 logits and all stores are coalesced.
+template <int D, int GPAD>
+__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p, int gb) {
+  constexpr int CH = D / 8;         // 16-byte chunks per token
+  constexpr int TPL = 64 / CH;      // tokens per coalesced wave load
+  constexpr int NLOAD = 64 / TPL;   // loads per 64-token block
+  constexpr int KSTEPS = D / 32;    // MFMA k-steps per tile
+  constexpr int TILES = 16 / GPAD;  // 16-token tiles per accumulator
+  constexpr int NACC = 4 / TILES;   // accumulators per block
+
+  __shared__ uint4 lds[kScoreWaves][64 * CH];
+  __shared__ float2 part[kScoreWaves][4][4];
+
+  const int row = blockIdx.y;
+  const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tq = lane / CH, cl = lane % CH;  // load role: token sub-index, chunk
+  const int n = lane & 15, j = lane >> 4;    // MFMA role: column (token), k-group / row block
+  const int64_t L = p.geo.L;
+  uint4* buf = lds[wave];
+
+  const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
+  const int64_t tok_bytes = p.ks_token * 2;
+
+  // A operand: lane (row m = n, k-group j) holds q[head m % GPAD][8*(4*kc + j) ..+8]
+  const int my_head = n % GPAD, my_slot = n / GPAD;
+  uint4 qa[KSTEPS];
+#pragma unroll
+  for (int kc = 0; kc < KSTEPS; ++kc) {
+    qa[kc] = make_uint4(0u, 0u, 0u, 0u);
+    if (my_head < gb) {
+      const int h = c * p.geo.G + p.g0 + my_head;
+      qa[kc] = ld16((const char*)p.q_last + (((int64_t)prob * p.geo.Hq + h) * D + (4 * kc + j) * 8) * 2);
+    }
+  }
+
+  // each lane ends up with the logits of heads hbase .. hbase+3
+  const int hbase = (4 * j) % GPAD;
+  float m[4], sum[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    m[r] = -INFINITY;
+    sum[r] = 0.f;
+  }
+
+  // Software pipeline: the loads of block b+1 are issued right after block b went to LDS, so
+  // their latency overlaps block b's MFMA phase.  The logits stay in registers until the wave
+  // has loaded its last block: loads and stores share one in-order completion counter, so a
+  // store inside the loop would put its write-ack latency on the critical path of every block.
+  const int64_t wave_base = (int64_t)blockIdx.x * kScoreChunk + (int64_t)wave * kBlocksPerWave * 64;
+  uint4 kv[NLOAD];
+  if (wave_base < L) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      int64_t tok = wave_base + i * TPL + tq;
+      tok = tok < L ? tok : L - 1;  // tail: re-read the last token, masked below
+      kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
+    }
+  }
+  float xs[kBlocksPerWave][NACC][4];
+#pragma unroll
+  for (int blk = 0; blk < kBlocksPerWave; ++blk) {
+    const int64_t tok_base = wave_base + (int64_t)blk * 64;
+    if (tok_base < L) {  // wave-uniform
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // previous block's LDS reads are done
+#pragma unroll
+      for (int i = 0; i < NLOAD; ++i) {
+        const int t = i * TPL + tq;
+        buf[t * CH + (cl ^ (t & (CH - 1)))] = kv[i];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      if (blk + 1 < kBlocksPerWave && tok_base + 64 < L) {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+          int64_t tok = tok_base + 64 + i * TPL + tq;
+          tok = tok < L ? tok : L - 1;
+          kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
+        }
+      }
+      f32x4_t acc[NACC];
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) {
+        acc[a] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ts = 0; ts < TILES; ++ts) {
+          const int t = (a * TILES + ts) * 16 + n;
+#pragma unroll
+          for (int kc = 0; kc < KSTEPS; ++kc) {
+            const uint4 b = buf[t * CH + ((4 * kc + j) ^ (n & (CH - 1)))];
+            const uint4 qv = (my_slot == ts) ? qa[kc] : make_uint4(0u, 0u, 0u, 0u);
+            acc[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qv),
+                                                             __builtin_bit_cast(bf16x8_t, b), acc[a], 0, 0, 0);
+          }
+        }
+      }
+      // lane (j, n), accumulator a, register r: row 4j + r = (tile slot, head), column n = token
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) {
+        const int64_t tok = tok_base + (a * TILES + (4 * j) / GPAD) * 16 + n;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float x = acc[a][r] * p.scale;
+          xs[blk][a][r] = x;
+          if (tok < L && hbase + r < gb) {
+            const float mn = fmaxf(m[r], x);
+            sum[r] = sum[r] * exp_fast(m[r] - mn) + exp_fast(x - mn);
+            m[r] = mn;
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int blk = 0; blk < kBlocksPerWave; ++blk) {
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) {
+      const int64_t tok = wave_base + (int64_t)blk * 64 + (a * TILES + (4 * j) / GPAD) * 16 + n;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (tok < L && hbase + r < gb)
+          p.logits[logit_index(p.geo, p.n_chunks, row, p.g0 + hbase + r, tok)] = xs[blk][a][r];
+    }
+  }
+
+  // (max, sum) of the chunk: the 16 lanes of a row block share their heads
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float M = m[r];
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    float s = (m[r] == -INFINITY) ? 0.f : sum[r] * exp_fast(m[r] - M);
+    s = group_sum<16>(s);
+    if (n == 0) part[wave][j][r] = make_float2(M, s);
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < gb) {
+    const int g = threadIdx.x;
+    float M = -INFINITY;
+    for (int w = 0; w < kScoreWaves; ++w)
+      for (int jj = 0; jj < 4; ++jj)
+        if ((4 * jj) % GPAD == (g / 4) * 4) M = fmaxf(M, part[w][jj][g % 4].x);
+    float s = 0.f;
+    for (int w = 0; w < kScoreWaves; ++w)
+      for (int jj = 0; jj < 4; ++jj)
+        if ((4 * jj) % GPAD == (g / 4) * 4) {
+          const float2 pw = part[w][jj][g % 4];
+          s += (pw.x == -INFINITY) ? 0.f : pw.y * exp_fast(pw.x - M);
+        }
     p.partials[((int64_t)row * p.geo.G + p.g0 + g) * p.n_chunks + blockIdx.x] = make_float2(M, s);
   }
 }
@@ -148,7 +314,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
   __shared__ float sM[kMaxG], sInv[kMaxG];
   const int row = blockIdx.y, tid = threadIdx.x;
   const int G = p.geo.G;
-  const int64_t L = p.geo.L, Lp = p.geo.Lp;
+  const int64_t L = p.geo.L;
   for (int b = tid; b < kHistBins; b += kCombineThreads) hist[b] = 0;
   if (tid < G) {
     RowStat st = p.stats[(int64_t)row * G + tid];
@@ -156,7 +322,6 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     sInv[tid] = st.invZ;
   }
   __syncthreads();
-  const float* lg = p.logits + (int64_t)row * G * Lp;
   float* out = p.scores + (int64_t)row * p.pitch;
   const int64_t cand_lo = p.S, cand_hi = L - p.W;
   const bool vec_out = (p.pitch & 3) == 0;
@@ -167,7 +332,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     if (tok >= L) break;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int g = 0; g < G; ++g) {
-      const float4 x = *reinterpret_cast<const float4*>(lg + (int64_t)g * Lp + tok);
+      const float4 x = *reinterpret_cast<const float4*>(p.logits + logit_index(p.geo, p.n_chunks, row, g, tok));
       const float M = sM[g], inv = sInv[g];
       acc[0] += exp_accurate(x.x - M) * inv;
       acc[1] += exp_accurate(x.y - M) * inv;
@@ -215,16 +380,28 @@ hipError_t launch_score_g(const ScoreParams& p, int gb, dim3 grid, hipStream_t s
 
 int max_group_per_launch() { return 8; }
 
+template <int D>
+hipError_t launch_score_mfma(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
+  if (gb <= 4)
+    hipLaunchKernelGGL((score_mfma_kernel<D, 4>), grid, dim3(kScoreThreads), 0, s, p, gb);
+  else if (gb <= 8)
+    hipLaunchKernelGGL((score_mfma_kernel<D, 8>), grid, dim3(kScoreThreads), 0, s, p, gb);
+  else
+    hipLaunchKernelGGL((score_mfma_kernel<D, 16>), grid, dim3(kScoreThreads), 0, s, p, gb);
+  return hipGetLastError();
+}
+
 hipError_t launch_score(const ScoreParams& p0, hipStream_t s) {
   const int rows = p0.geo.n_problems * p0.geo.Hkv;
   dim3 grid((unsigned)p0.n_chunks, (unsigned)rows);
-  for (int g0 = 0; g0 < p0.geo.G; g0 += max_group_per_launch()) {
+  const int per_launch = p0.geo.dtype == DT_BF16 ? 16 : max_group_per_launch();
+  for (int g0 = 0; g0 < p0.geo.G; g0 += per_launch) {
     ScoreParams p = p0;
     p.g0 = g0;
-    const int gb = p0.geo.G - g0 < max_group_per_launch() ? p0.geo.G - g0 : max_group_per_launch();
+    const int gb = p0.geo.G - g0 < per_launch ? p0.geo.G - g0 : per_launch;
     hipError_t e;
     if (p.geo.dtype == DT_BF16)
-      e = p.geo.D == 128 ? launch_score_g<DT_BF16, 128>(p, gb, grid, s) : launch_score_g<DT_BF16, 64>(p, gb, grid, s);
+      e = p.geo.D == 128 ? launch_score_mfma<128>(p, gb, grid, s) : launch_score_mfma<64>(p, gb, grid, s);
     else
       e = p.geo.D == 128 ? launch_score_g<DT_F32, 128>(p, gb, grid, s) : launch_score_g<DT_F32, 64>(p, gb, grid, s);
     if (e != hipSuccess) return e;
