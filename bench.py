@@ -175,7 +175,8 @@ def main():
     sel_gbps = sel_b / (sel_ms * 1e-3) / 1e9
     dec_tok_s = (n_dec * cfg.batch) / (dec_ms * 1e-3) if n_dec else None
     dec_gbps = (n_dec * dec_b) / (dec_ms * 1e-3) / 1e9 if n_dec else None
-    score_ms = float(stage_ms[0])
+    score_ms = float(stage_ms[sk.binding.STAGES.index("score")])
+    redone = sk.sagekv_select_redone_rows(sdesc, sws)
     score_gbps = score_b / (score_ms * 1e-3) / 1e9
 
     result = {
@@ -199,7 +200,7 @@ def main():
         },
         "frac_hbm": round(value / HBM_PEAK_GBPS, 4),
         "select": {"ms": round(sel_ms, 4), "GBps": round(sel_gbps, 1), "frac_hbm": round(sel_gbps / HBM_PEAK_GBPS, 4),
-                   "algorithmic_bytes": sel_b,
+                   "algorithmic_bytes": sel_b, "rows_redone_by_dense_path": redone,
                    "stage_ms": {n: round(float(v), 4) for n, v in zip(sk.binding.STAGES, stage_ms)}},
         "decode": {"tokens_per_s": None if dec_tok_s is None else round(dec_tok_s, 1),
                    "ms_per_token": None if not n_dec else round(dec_ms / n_dec, 5),

@@ -72,7 +72,16 @@ typedef struct {
   int32_t n_recent;            /* W >= 1, includes the last token                          */
   int32_t k;                   /* middle tokens kept per row, 0 <= k <= L - S - W          */
   int32_t compact_capacity;    /* row pitch (tokens) of Kc / Vc, >= S + k + W              */
+  uint32_t flags;              /* 0, or SAGEKV_SELECT_DENSE                                */
 } sagekv_select_desc;
+
+/* sagekv_select normally pre-filters: a strided sample of each row gives a conservative score
+ * threshold, the pass over K keeps only the tokens that reach it, and the top-k is taken among
+ * those; a row whose result cannot be proven equal to the top-k over ALL its candidates is redone
+ * by the dense path (every token's score is materialised).  The kept set is the same either way.
+ * SAGEKV_SELECT_DENSE forces the dense path for every row; so does a non-null scores_out, an
+ * fp32 cache, G > 16, more than 524288 candidates per row, or 5 k + 8192 > L - S - W. */
+enum { SAGEKV_SELECT_DENSE = 1u };
 
 /* Bytes of device scratch sagekv_select needs for this descriptor (0 if it is invalid). */
 size_t sagekv_select_workspace_bytes(const sagekv_select_desc* desc);
@@ -92,6 +101,12 @@ size_t sagekv_select_workspace_bytes(const sagekv_select_desc* desc);
 sagekv_status sagekv_select(const sagekv_select_desc* desc, const void* q_last, const void* K, const void* V,
                             void* Kc, void* Vc, int32_t* kept_idx, float* scores_out, void* workspace,
                             size_t workspace_bytes, void* hip_stream);
+
+/* Test / benchmark aid: waits for the stream, then reports how many rows of the LAST sagekv_select
+ * call that used this workspace were redone by the dense path (-1 if the call was dense anyway).
+ * `n_rows` is a host pointer. */
+sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* desc, const void* workspace,
+                                        size_t workspace_bytes, void* hip_stream, int32_t* n_rows);
 
 /* ---- decoding over the reduced cache -------------------------------------------------- */
 typedef struct {
@@ -139,9 +154,9 @@ const char* sagekv_status_string(sagekv_status s); /* host string, static storag
  * destroys the events).  While enabled, each call records an event pair around every stage's
  * launches on the call's own stream.  sagekv_stage_timing_read(which, call, ms) waits for that
  * call's events and returns the elapsed milliseconds per stage: which = 0 reads a select call
- * (ms[SAGEKV_STAGE_SCORE .. SAGEKV_STAGE_GATHER]), which = 1 a decode call (ms[0] only). */
-enum { SAGEKV_STAGE_SCORE = 0, SAGEKV_STAGE_STATS = 1, SAGEKV_STAGE_COMBINE = 2, SAGEKV_STAGE_TOPK = 3,
-       SAGEKV_STAGE_GATHER = 4, SAGEKV_N_STAGES = 5 };
+ * (ms[0 .. SAGEKV_N_STAGES), 0 for a stage the call did not run), which = 1 a decode call (ms[0] only). */
+enum { SAGEKV_STAGE_SAMPLE = 0, SAGEKV_STAGE_SCORE = 1, SAGEKV_STAGE_STATS = 2, SAGEKV_STAGE_COMBINE = 3,
+       SAGEKV_STAGE_TOPK = 4, SAGEKV_STAGE_REDO = 5, SAGEKV_STAGE_GATHER = 6, SAGEKV_N_STAGES = 7 };
 sagekv_status sagekv_stage_timing_enable(int32_t n_calls);
 sagekv_status sagekv_stage_timing_read(int32_t which, int32_t call, float* ms /* host */);
 

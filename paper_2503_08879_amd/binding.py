@@ -14,10 +14,12 @@ LIB_PATH = os.path.join(_HERE, "libsagekv.so")
 
 BF16, F32 = 0, 1
 GROUP_SUM, PER_QUERY = 0, 1
-STAGES = ("score", "stats", "combine", "topk", "gather")
+STAGES = ("sample", "score", "stats", "combine", "topk", "redo", "gather")
+SELECT_DENSE = 1
 
 EXPORTS = (
-    "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_append",
+    "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_select_redone_rows",
+    "sagekv_append",
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read",
 )
@@ -31,7 +33,7 @@ class SelectDesc(ctypes.Structure):
         ("k_stride_problem", ctypes.c_int64), ("k_stride_head", ctypes.c_int64), ("k_stride_token", ctypes.c_int64),
         ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
         ("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32), ("k", ctypes.c_int32),
-        ("compact_capacity", ctypes.c_int32),
+        ("compact_capacity", ctypes.c_int32), ("flags", ctypes.c_uint32),
     ]
 
 
@@ -67,6 +69,8 @@ def lib():
         L.sagekv_select_workspace_bytes.argtypes = [ctypes.POINTER(SelectDesc)]
         L.sagekv_select.restype = ctypes.c_int
         L.sagekv_select.argtypes = [ctypes.POINTER(SelectDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.sagekv_select_redone_rows.restype = ctypes.c_int
+        L.sagekv_select_redone_rows.argtypes = [ctypes.POINTER(SelectDesc), vp, sz, vp, ctypes.POINTER(i32)]
         L.sagekv_append.restype = ctypes.c_int
         L.sagekv_append.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, i32, vp]
         L.sagekv_decode_workspace_bytes.restype = sz
@@ -113,14 +117,14 @@ def _check(code: int, what: str):
 
 
 # ---------------------------------------------------------------------------------------- select
-def select_desc(q_last, K, V, n_sink, n_recent, k, compact_capacity=None, head_mode=GROUP_SUM) -> SelectDesc:
+def select_desc(q_last, K, V, n_sink, n_recent, k, compact_capacity=None, head_mode=GROUP_SUM, flags=0) -> SelectDesc:
     """Descriptor for q_last [P,Hq,d] and K, V [P,Hkv,L,d] (any strides with a unit inner stride)."""
     P, Hq, d = q_last.shape
     _, Hkv, L, _ = K.shape
     assert K.stride(3) == 1 and V.stride(3) == 1 and q_last.is_contiguous()
     cap = n_sink + k + n_recent if compact_capacity is None else compact_capacity
     return SelectDesc(P, Hq, Hkv, d, _dtype_of(K), head_mode, L, K.stride(0), K.stride(1), K.stride(2),
-                      V.stride(0), V.stride(1), V.stride(2), n_sink, n_recent, k, cap)
+                      V.stride(0), V.stride(1), V.stride(2), n_sink, n_recent, k, cap, flags)
 
 
 def sagekv_select_workspace_bytes(desc: SelectDesc) -> int:
@@ -133,6 +137,14 @@ def sagekv_select(desc: SelectDesc, q_last, K, V, Kc, Vc, kept_idx, scores_out, 
                                _ptr(kept_idx), _ptr(scores_out), _ptr(workspace),
                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(code, "sagekv_select")
+
+
+def sagekv_select_redone_rows(desc: SelectDesc, workspace) -> int:
+    """Rows of the last sagekv_select on this workspace that the dense path had to redo (-1: dense call)."""
+    n = ctypes.c_int32(0)
+    _check(lib().sagekv_select_redone_rows(ctypes.byref(desc), _ptr(workspace), _ws_bytes(workspace), _stream(),
+                                           ctypes.byref(n)), "sagekv_select_redone_rows")
+    return n.value
 
 
 # ---------------------------------------------------------------------------------------- decode

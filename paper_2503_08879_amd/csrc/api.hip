@@ -2,6 +2,7 @@
 #include "../../include/sagekv.h"
 
 #include <math.h>
+
 #include <vector>
 
 #include "kernels.h"
@@ -19,8 +20,42 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // of magnitude of margin while the band still holds only a handful of candidates per row.
 constexpr float kBand = 1.0f / 4096.0f;
 
+// Sizes of the fast (pre-filtered) eviction path for one descriptor; ok = the path applies.
+struct FastPlan {
+  bool ok;
+  int n_sink_s, n_cand_s, n_recent_s, rank, cap, Gs;
+};
+
+FastPlan fast_plan(const sagekv_select_desc* d) {
+  FastPlan f = {};
+  const int G = d->n_q_heads / d->n_kv_heads;
+  const int64_t E = d->L - d->n_sink - d->n_recent;
+  f.ok = d->dtype == SAGEKV_BF16 && G <= 16 && d->k > 0 && E <= 524288 && d->L <= 1024 * (int64_t)kScoreChunk &&
+         !(d->flags & SAGEKV_SELECT_DENSE);
+  if (!f.ok) return f;
+  f.cap = (int)(2.5 * d->k) + 4096;
+  if ((int64_t)f.cap * 2 > E) {  // k is a large share of the row: the filter would keep most of it
+    f.ok = false;
+    return f;
+  }
+  int64_t target = E / 32;
+  target = target < 1024 ? 1024 : (target > 8192 ? 8192 : target);
+  f.n_cand_s = (int)(E < target ? E : target);
+  f.n_sink_s = d->n_sink < 64 ? d->n_sink : 64;
+  f.n_recent_s = d->n_recent < 256 ? d->n_recent : 256;
+  // threshold = sample quantile that about 1.5 k tokens of the row exceed, plus 3 sigma of its rank
+  const double r = 1.5 * (double)d->k * (double)f.n_cand_s / (double)E;
+  f.rank = (int)ceil(r + 3.0 * sqrt(r) + 1.0);
+  f.Gs = (G + 3) / 4 * 4;
+  return f;
+}
+
 struct SelectLayout {
   size_t logits, scores, partials, stats, ghist, total;
+  // fast path
+  size_t samp_logit, samp_score, samp_stats, samp_tau, cand_count, cand_idx, cand_logit, cand_score, cand_pos, bound,
+      row_fail, fail_list, n_fail;
+  FastPlan fast;
   int64_t Lp;
   int n_chunks, rows, G;
 };
@@ -34,6 +69,7 @@ bool check_select(const sagekv_select_desc* d, sagekv_status* st) {
   if ((int64_t)d->n_sink + d->n_recent + d->k > d->L) return false;
   if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + d->k) return false;
   if ((int64_t)d->n_problems * d->n_kv_heads > 65535) return false;
+  if (d->flags & ~(uint32_t)SAGEKV_SELECT_DENSE) return false;
   *st = SAGEKV_ERR_UNSUPPORTED;
   if (d->dtype != SAGEKV_BF16 && d->dtype != SAGEKV_F32) return false;
   if (d->head_dim != 64 && d->head_dim != 128) return false;
@@ -49,23 +85,45 @@ bool check_select(const sagekv_select_desc* d, sagekv_status* st) {
   return true;
 }
 
+// The workspace always holds the dense path's scratch (rows the fast path cannot certify are
+// redone there); a caller-provided scores_out replaces the score rows.
 SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   SelectLayout l;
   l.rows = d->n_problems * d->n_kv_heads;
   l.G = d->n_q_heads / d->n_kv_heads;
   l.Lp = (d->L + 3) / 4 * 4;
   l.n_chunks = (int)((d->L + kScoreChunk - 1) / kScoreChunk);
+  l.fast = fast_plan(d);
   size_t off = 0;
-  l.logits = off;
-  off = align_up(off + (size_t)l.rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
-  l.scores = off;
-  if (own_scores) off = align_up(off + (size_t)l.rows * l.Lp * sizeof(float));
-  l.partials = off;
-  off = align_up(off + (size_t)l.rows * l.G * l.n_chunks * sizeof(float2));
-  l.stats = off;
-  off = align_up(off + (size_t)l.rows * l.G * sizeof(RowStat));
-  l.ghist = off;
-  off = align_up(off + (size_t)l.rows * kHistBins * sizeof(int));
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes);
+    return at;
+  };
+  const size_t rows = (size_t)l.rows;
+  l.logits = take(rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
+  l.scores = take(own_scores ? rows * l.Lp * sizeof(float) : 0);
+  l.partials = take(rows * l.G * l.n_chunks * sizeof(float2));
+  l.stats = take(rows * l.G * sizeof(RowStat));
+  l.ghist = take(rows * kHistBins * sizeof(int));
+  if (l.fast.ok) {
+    const FastPlan& f = l.fast;
+    const size_t ns = (size_t)f.n_sink_s + f.n_cand_s + f.n_recent_s;
+    l.samp_logit = take(rows * ns * l.G * sizeof(float));
+    l.samp_score = take(rows * f.n_cand_s * sizeof(float));
+    l.samp_stats = take(rows * l.G * sizeof(float2));
+    l.samp_tau = take(rows * sizeof(float));
+    const size_t slots = rows * l.n_chunks * kScoreChunk;  // every token has a slot: chunks cannot overflow
+    l.cand_count = take(rows * l.n_chunks * sizeof(int));
+    l.cand_idx = take(slots * sizeof(int32_t));
+    l.cand_logit = take(slots * f.Gs * sizeof(float));
+    l.cand_score = take(rows * f.cap * sizeof(float));
+    l.cand_pos = take(rows * f.cap * sizeof(int32_t));
+    l.bound = take(rows * sizeof(float));
+    l.row_fail = take(rows * sizeof(int));
+    l.fail_list = take(rows * sizeof(int));
+    l.n_fail = take(sizeof(int));
+  }
   l.total = off;
   return l;
 }
@@ -121,15 +179,20 @@ struct Timing {
   int next_select = 0, next_decode = 0;
   std::vector<hipEvent_t> sel;  // [n_calls][SAGEKV_N_STAGES][2]
   std::vector<hipEvent_t> dec;  // [n_calls][2]
+  std::vector<uint32_t> sel_mask;  // [n_calls] stages that recorded both events
 } g_timing;
 
 struct StageTimer {
   hipEvent_t* ev = nullptr;
+  uint32_t* mask = nullptr;
   hipStream_t s;
   StageTimer(int which, hipStream_t stream) : s(stream) {
     if (g_timing.n_calls == 0) return;
-    if (which == 0 && g_timing.next_select < g_timing.n_calls)
+    if (which == 0 && g_timing.next_select < g_timing.n_calls) {
+      mask = &g_timing.sel_mask[g_timing.next_select];
+      *mask = 0;
       ev = &g_timing.sel[(size_t)g_timing.next_select++ * SAGEKV_N_STAGES * 2];
+    }
     if (which == 1 && g_timing.next_decode < g_timing.n_calls) ev = &g_timing.dec[(size_t)g_timing.next_decode++ * 2];
   }
   void begin(int stage) {
@@ -137,6 +200,7 @@ struct StageTimer {
   }
   void end(int stage) {
     if (ev) (void)hipEventRecord(ev[stage * 2 + 1], s);
+    if (mask) *mask |= 1u << stage;
   }
 };
 
@@ -208,6 +272,8 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   if (!workspace || workspace_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
+  // per-token scores are only produced by the dense path
+  const bool fast = l.fast.ok && scores_out == nullptr;
 
   RowGeom geo;
   geo.n_problems = d->n_problems;
@@ -225,11 +291,13 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   float2* partials = (float2*)(ws + l.partials);
   RowStat* stats = (RowStat*)(ws + l.stats);
   int* ghist = (int*)(ws + l.ghist);
+  const float scale = (float)(1.0 / sqrt((double)d->head_dim));
 
   StageTimer t(0, s);
   hipError_t e;
+  RowGate gate = {nullptr, nullptr};
 
-  ScoreParams sp;
+  ScoreParams sp = {};
   sp.geo = geo;
   sp.q_last = q_last;
   sp.K = K;
@@ -240,25 +308,125 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   sp.partials = partials;
   sp.n_chunks = l.n_chunks;
   sp.g0 = 0;
-  sp.scale = (float)(1.0 / sqrt((double)d->head_dim));
-  t.begin(SAGEKV_STAGE_SCORE);
-  e = launch_score(sp, s);
-  t.end(SAGEKV_STAGE_SCORE);
-  if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+  sp.scale = scale;
 
-  StatsParams tp;
+  StatsParams tp = {};
   tp.partials = partials;
   tp.stats = stats;
-  tp.ghist = ghist;
   tp.G = l.G;
   tp.n_chunks = l.n_chunks;
-  t.begin(SAGEKV_STAGE_STATS);
-  e = launch_stats(tp, l.rows, s);
-  t.end(SAGEKV_STAGE_STATS);
+
+  if (fast) {
+    const FastPlan& f = l.fast;
+    float2* samp_stats = (float2*)(ws + l.samp_stats);
+    float* samp_tau = (float*)(ws + l.samp_tau);
+    int* cand_count = (int*)(ws + l.cand_count);
+    int32_t* cand_idx = (int32_t*)(ws + l.cand_idx);
+    float* cand_logit = (float*)(ws + l.cand_logit);
+    float* bound = (float*)(ws + l.bound);
+    int* row_fail = (int*)(ws + l.row_fail);
+    int* fail_list = (int*)(ws + l.fail_list);
+    int* n_fail = (int*)(ws + l.n_fail);
+
+    SampleParams mp = {};
+    mp.geo = geo;
+    mp.q_last = q_last;
+    mp.K = K;
+    mp.ks_problem = d->k_stride_problem;
+    mp.ks_head = d->k_stride_head;
+    mp.ks_token = d->k_stride_token;
+    mp.S = d->n_sink;
+    mp.W = d->n_recent;
+    mp.k = d->k;
+    mp.n_sink_s = f.n_sink_s;
+    mp.n_cand_s = f.n_cand_s;
+    mp.n_recent_s = f.n_recent_s;
+    mp.rank = f.rank;
+    mp.samp_logit = (float*)(ws + l.samp_logit);
+    mp.samp_score = (float*)(ws + l.samp_score);
+    mp.samp_stats = samp_stats;
+    mp.samp_tau = samp_tau;
+    mp.row_fail = row_fail;
+    mp.scale = scale;
+    t.begin(SAGEKV_STAGE_SAMPLE);
+    e = launch_sample(mp, s);
+    t.end(SAGEKV_STAGE_SAMPLE);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+
+    ScoreParams fp = sp;
+    fp.filt.samp_stats = samp_stats;
+    fp.filt.samp_tau = samp_tau;
+    fp.filt.cand_count = cand_count;
+    fp.filt.cand_idx = cand_idx;
+    fp.filt.cand_logit = cand_logit;
+    fp.filt.Gs = f.Gs;
+    fp.filt.S = d->n_sink;
+    fp.filt.W = d->n_recent;
+    t.begin(SAGEKV_STAGE_SCORE);
+    e = launch_score_filter(fp, s);
+    t.end(SAGEKV_STAGE_SCORE);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+
+    StatsParams ft = tp;
+    ft.ghist = nullptr;
+    ft.samp_stats = samp_stats;
+    ft.samp_tau = samp_tau;
+    ft.bound = bound;
+    t.begin(SAGEKV_STAGE_STATS);
+    e = launch_stats(ft, l.rows, s);
+    t.end(SAGEKV_STAGE_STATS);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+
+    TopkCandParams cp = {};
+    cp.geo = geo;
+    cp.stats = stats;
+    cp.bound = bound;
+    cp.cand_count = cand_count;
+    cp.cand_idx = cand_idx;
+    cp.cand_logit = cand_logit;
+    cp.n_chunks = l.n_chunks;
+    cp.cand_score = (float*)(ws + l.cand_score);
+    cp.cand_pos = (int32_t*)(ws + l.cand_pos);
+    cp.cap = f.cap;
+    cp.Gs = f.Gs;
+    cp.q_last = q_last;
+    cp.K = K;
+    cp.ks_problem = d->k_stride_problem;
+    cp.ks_head = d->k_stride_head;
+    cp.ks_token = d->k_stride_token;
+    cp.kept_idx = kept_idx;
+    cp.row_fail = row_fail;
+    cp.S = d->n_sink;
+    cp.W = d->n_recent;
+    cp.k = d->k;
+    cp.band = kBand;
+    t.begin(SAGEKV_STAGE_TOPK);
+    e = launch_topk_cand(cp, s);
+    if (e == hipSuccess) e = launch_collect_failed(row_fail, l.rows, fail_list, n_fail, s);
+    t.end(SAGEKV_STAGE_TOPK);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    gate.row_map = fail_list;  // the dense stages below only run for the rows that were flagged
+    gate.n_active = n_fail;
+    t.begin(SAGEKV_STAGE_REDO);
+  }
+
+  // ---- dense path: every row, or the rows the fast path flagged
+  sp.gate = gate;
+  if (!fast) t.begin(SAGEKV_STAGE_SCORE);
+  e = launch_score(sp, s);
+  if (!fast) t.end(SAGEKV_STAGE_SCORE);
   if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
 
-  CombineParams cp;
+  tp.gate = gate;
+  tp.ghist = ghist;
+  if (!fast) t.begin(SAGEKV_STAGE_STATS);
+  e = launch_stats(tp, l.rows, s);
+  if (!fast) t.end(SAGEKV_STAGE_STATS);
+  if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+
+  CombineParams cp = {};
   cp.geo = geo;
+  cp.gate = gate;
   cp.logits = logits;
   cp.n_chunks = l.n_chunks;
   cp.stats = stats;
@@ -267,13 +435,14 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   cp.ghist = ghist;
   cp.S = d->n_sink;
   cp.W = d->n_recent;
-  t.begin(SAGEKV_STAGE_COMBINE);
+  if (!fast) t.begin(SAGEKV_STAGE_COMBINE);
   e = launch_combine(cp, s);
-  t.end(SAGEKV_STAGE_COMBINE);
+  if (!fast) t.end(SAGEKV_STAGE_COMBINE);
   if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
 
-  TopkParams kp;
+  TopkParams kp = {};
   kp.geo = geo;
+  kp.gate = gate;
   kp.scores = scores;
   kp.pitch = pitch;
   kp.ghist = ghist;
@@ -288,12 +457,13 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   kp.W = d->n_recent;
   kp.k = d->k;
   kp.band = kBand;
-  t.begin(SAGEKV_STAGE_TOPK);
+  if (!fast) t.begin(SAGEKV_STAGE_TOPK);
   e = launch_topk(kp, s);
-  t.end(SAGEKV_STAGE_TOPK);
+  if (!fast) t.end(SAGEKV_STAGE_TOPK);
+  if (fast) t.end(SAGEKV_STAGE_REDO);
   if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
 
-  GatherParams gp;
+  GatherParams gp = {};
   gp.geo = geo;
   gp.K = K;
   gp.V = V;
@@ -312,6 +482,24 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   e = launch_gather(gp, s);
   t.end(SAGEKV_STAGE_GATHER);
   return dev(e);
+}
+
+sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* d, const void* workspace, size_t workspace_bytes,
+                                        void* hip_stream, int32_t* n_rows) {
+  sagekv_status st;
+  if (!check_select(d, &st)) return st;
+  if (!n_rows) return SAGEKV_ERR_INVALID_ARG;
+  const SelectLayout l = select_layout(d, true);
+  if (!workspace || workspace_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
+  *n_rows = -1;
+  if (!l.fast.ok) return SAGEKV_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (hipStreamSynchronize(s) != hipSuccess) return SAGEKV_ERR_DEVICE;
+  int v = 0;
+  if (hipMemcpy(&v, (const char*)workspace + l.n_fail, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
+    return SAGEKV_ERR_DEVICE;
+  *n_rows = v;
+  return SAGEKV_OK;
 }
 
 sagekv_status sagekv_append(const sagekv_decode_desc* d, const void* k_new, const void* v_new, void* Kc, void* Vc,
@@ -370,11 +558,13 @@ sagekv_status sagekv_stage_timing_enable(int32_t n_calls) {
   for (hipEvent_t e : g_timing.dec) (void)hipEventDestroy(e);
   g_timing.sel.clear();
   g_timing.dec.clear();
+  g_timing.sel_mask.clear();
   g_timing.n_calls = 0;
   g_timing.next_select = g_timing.next_decode = 0;
   if (n_calls <= 0) return SAGEKV_OK;
   g_timing.sel.resize((size_t)n_calls * SAGEKV_N_STAGES * 2);
   g_timing.dec.resize((size_t)n_calls * 2);
+  g_timing.sel_mask.assign((size_t)n_calls, 0u);
   for (hipEvent_t& e : g_timing.sel)
     if (hipEventCreate(&e) != hipSuccess) return SAGEKV_ERR_DEVICE;
   for (hipEvent_t& e : g_timing.dec)
@@ -389,6 +579,8 @@ sagekv_status sagekv_stage_timing_read(int32_t which, int32_t call, float* ms) {
     if (call >= g_timing.next_select) return SAGEKV_ERR_INVALID_ARG;
     hipEvent_t* ev = &g_timing.sel[(size_t)call * SAGEKV_N_STAGES * 2];
     for (int i = 0; i < SAGEKV_N_STAGES; ++i) {
+      ms[i] = 0.f;
+      if (!(g_timing.sel_mask[call] & (1u << i))) continue;
       if (hipEventSynchronize(ev[2 * i + 1]) != hipSuccess) return SAGEKV_ERR_DEVICE;
       if (hipEventElapsedTime(&ms[i], ev[2 * i], ev[2 * i + 1]) != hipSuccess) return SAGEKV_ERR_DEVICE;
     }

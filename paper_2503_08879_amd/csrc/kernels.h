@@ -24,8 +24,31 @@ struct RowGeom {
   int64_t Lp;  // pitch (floats) of the logit rows, multiple of 4
 };
 
+// Rows a gated launch works on: row = row_map[blockIdx] while blockIdx < *n_active (both device
+// memory).  Null row_map = all rows, identity.
+struct RowGate {
+  const int* row_map;
+  const int* n_active;
+};
+
+// Candidate pre-filter of the fast eviction path.  A strided sample of the row gives approximate
+// softmax statistics and a conservative score threshold; the streaming score pass then keeps
+// only the tokens whose approximate score passes it (index + exact fp32 logits), instead of
+// writing every token's logits.
+struct FilterParams {
+  const float2* samp_stats;  // [rows][G]  (M^, 1/Z^) from the sample
+  const float* samp_tau;     // [rows]     threshold on the approximate score
+  int* cand_count;           // [rows][n_chunks]               candidates each score workgroup kept
+  int32_t* cand_idx;         // [rows][n_chunks][kScoreChunk]  a workgroup owns its chunk's slots: no
+  float* cand_logit;         // [rows][n_chunks][kScoreChunk][Gs]   global atomics, no overflow
+  int Gs;
+  int S, W;
+};
+
 struct ScoreParams {
   RowGeom geo;
+  RowGate gate;
+  FilterParams filt;  // used by the filtering variant only
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;  // elements
@@ -37,14 +60,20 @@ struct ScoreParams {
 };
 
 struct StatsParams {
+  RowGate gate;
   const float2* partials;
   RowStat* stats;  // [rows][G]
-  int* ghist;      // [rows][kHistBins], zeroed here
+  int* ghist;      // [rows][kHistBins], zeroed here (nullable)
   int G, n_chunks;
+  // fast path (nullable): bound[row] = upper bound of the exact score of any token the filter dropped
+  const float2* samp_stats;
+  const float* samp_tau;
+  float* bound;
 };
 
 struct CombineParams {
   RowGeom geo;
+  RowGate gate;
   const float* logits;
   int n_chunks;  // score chunks per row (logit scratch layout)
   const RowStat* stats;
@@ -56,6 +85,7 @@ struct CombineParams {
 
 struct TopkParams {
   RowGeom geo;
+  RowGate gate;
   float* scores;
   int64_t pitch;
   const int* ghist;
@@ -66,6 +96,43 @@ struct TopkParams {
   int32_t* kept_idx;  // [rows][S + k + W]
   int S, W, k;
   float band;  // relative half-width of the fp64 re-evaluation band around the k-th score
+};
+
+struct SampleParams {
+  RowGeom geo;
+  const void* q_last;
+  const void* K;
+  int64_t ks_problem, ks_head, ks_token;
+  int S, W, k;
+  int n_sink_s, n_cand_s, n_recent_s;  // sample sizes of the three parts of the row
+  int rank;                            // rank (1-based) of the threshold among the sampled candidates
+  float* samp_logit;                   // [rows][n_samp][G] scratch
+  float* samp_score;                   // [rows][n_cand_s] scratch
+  float2* samp_stats;                  // out [rows][G]
+  float* samp_tau;                     // out [rows]
+  int* row_fail;                       // out [rows] = 0
+  float scale;
+};
+
+// Final selection of the fast path, on the candidate list of each row.
+struct TopkCandParams {
+  RowGeom geo;
+  const RowStat* stats;
+  const float* bound;
+  const int* cand_count;     // per score chunk, see FilterParams
+  const int32_t* cand_idx;
+  const float* cand_logit;
+  int n_chunks;
+  float* cand_score;         // [rows][cap] scratch: exact scores of the row's candidates, dense
+  int32_t* cand_pos;         // [rows][cap] scratch: their token indices
+  int cap, Gs;
+  const void* q_last;
+  const void* K;
+  int64_t ks_problem, ks_head, ks_token;
+  int32_t* kept_idx;
+  int* row_fail;  // set to 1 when the row must be redone by the general path
+  int S, W, k;
+  float band;
 };
 
 struct GatherParams {
@@ -95,6 +162,10 @@ struct DecodeParams {
   float scale;
 };
 
+hipError_t launch_sample(const SampleParams& p, hipStream_t s);
+hipError_t launch_score_filter(const ScoreParams& p, hipStream_t s);
+hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s);
+hipError_t launch_collect_failed(const int* row_fail, int rows, int* fail_list, int* n_fail, hipStream_t s);
 hipError_t launch_score(const ScoreParams& p, hipStream_t s);
 hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);

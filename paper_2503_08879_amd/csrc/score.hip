@@ -36,7 +36,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
   constexpr int TPL = 64 / LPT;
   constexpr int SB = LPT < 8 ? LPT : 8;  // loads in flight per batch
 
-  const int row = blockIdx.y;
+  int row = blockIdx.y;
+  if (p.gate.row_map) {
+    if ((int)blockIdx.y >= *p.gate.n_active) return;
+    row = p.gate.row_map[blockIdx.y];
+  }
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tq = lane / LPT, cl = lane % LPT;
@@ -130,7 +134,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
 // private, XOR-swizzled LDS buffer (conflict free both ways).  GPAD = heads padded to 4, 8 or
 // 16: 16/GPAD tiles share an accumulator (the queries of tile t sit in rows t*GPAD..), so after
 // a block every lane owns 4 logits and all stores are coalesced.
-template <int D, int GPAD>
+//
+// FILTER = true is the fast eviction path: nothing is written per token.  A lane keeps its logits
+// only for tokens whose approximate score (sample statistics) reaches the row's conservative
+// threshold, and appends (index, logits) to the row's candidate list.
+template <int D, int GPAD, bool FILTER>
 __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p, int gb) {
   constexpr int CH = D / 8;         // 16-byte chunks per token
   constexpr int TPL = 64 / CH;      // tokens per coalesced wave load
@@ -141,8 +149,13 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
 
   __shared__ uint4 lds[kScoreWaves][64 * CH];
   __shared__ float2 part[kScoreWaves][4][4];
+  __shared__ int n_kept_wg;  // FILTER: candidates this workgroup has kept so far
 
-  const int row = blockIdx.y;
+  int row = blockIdx.y;
+  if (p.gate.row_map) {
+    if ((int)blockIdx.y >= *p.gate.n_active) return;
+    row = p.gate.row_map[blockIdx.y];
+  }
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tq = lane / CH, cl = lane % CH;  // load role: token sub-index, chunk
@@ -174,6 +187,22 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
     sum[r] = 0.f;
   }
 
+  // filter state: approximate softmax weights of this lane's 4 heads, the row's threshold
+  float fM[4] = {0.f, 0.f, 0.f, 0.f}, fInv[4] = {0.f, 0.f, 0.f, 0.f}, ftau = 0.f;
+  if (FILTER) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (hbase + r < gb) {
+        const float2 st = p.filt.samp_stats[(int64_t)row * p.geo.G + hbase + r];
+        fM[r] = st.x;
+        fInv[r] = st.y;
+      }
+    ftau = p.filt.samp_tau[row];
+    if (threadIdx.x == 0) n_kept_wg = 0;
+    __syncthreads();
+  }
+  const int64_t slot_base = ((int64_t)row * p.n_chunks + blockIdx.x) * kScoreChunk;  // FILTER: this chunk's slots
+
   // Software pipeline: the loads of block b+1 are issued right after block b went to LDS, so
   // their latency overlaps block b's MFMA phase.  The logits stay in registers until the wave
   // has loaded its last block: loads and stores share one in-order completion counter, so a
@@ -188,7 +217,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
       kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
     }
   }
-  float xs[kBlocksPerWave][NACC][4];
+  float xs[FILTER ? 1 : kBlocksPerWave][NACC][4];
 #pragma unroll
   for (int blk = 0; blk < kBlocksPerWave; ++blk) {
     const int64_t tok_base = wave_base + (int64_t)blk * 64;
@@ -228,21 +257,43 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
 #pragma unroll
       for (int a = 0; a < NACC; ++a) {
         const int64_t tok = tok_base + (a * TILES + (4 * j) / GPAD) * 16 + n;
+        float approx = 0.f;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float x = acc[a][r] * p.scale;
-          xs[blk][a][r] = x;
+          xs[FILTER ? 0 : blk][a][r] = x;
           if (tok < L && hbase + r < gb) {
             const float mn = fmaxf(m[r], x);
             sum[r] = sum[r] * exp_fast(m[r] - mn) + exp_fast(x - mn);
             m[r] = mn;
+            if (FILTER) approx += exp_fast(x - fM[r]) * fInv[r];
+          }
+        }
+        if (FILTER) {
+          // the heads of a token sit in GPAD/4 lanes (same n, adjacent j): add their parts
+          if (GPAD >= 8) approx += __shfl_xor(approx, 16);
+          if (GPAD >= 16) approx += __shfl_xor(approx, 32);
+          const bool pass = tok >= p.filt.S && tok < L - p.filt.W && !(approx < ftau);
+          const bool rep = (4 * j) % GPAD == 0;  // one lane per token counts it
+          const unsigned long long bal = __ballot(pass && rep);
+          if (bal) {  // wave-uniform
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&n_kept_wg, __popcll(bal));  // LDS counter
+            base = __shfl(base, 0);
+            int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+            pos = __shfl(pos, ((j - j % (GPAD / 4)) << 4) | n);  // every lane of the token
+            if (pass && hbase < gb) {
+              if (rep) p.filt.cand_idx[slot_base + pos] = (int32_t)tok;
+              float* rec = p.filt.cand_logit + (slot_base + pos) * p.filt.Gs + hbase;
+              *reinterpret_cast<float4*>(rec) = make_float4(xs[0][a][0], xs[0][a][1], xs[0][a][2], xs[0][a][3]);
+            }
           }
         }
       }
     }
   }
 #pragma unroll
-  for (int blk = 0; blk < kBlocksPerWave; ++blk) {
+  for (int blk = 0; blk < (FILTER ? 0 : kBlocksPerWave); ++blk) {
 #pragma unroll
     for (int a = 0; a < NACC; ++a) {
       const int64_t tok = wave_base + (int64_t)blk * 64 + (a * TILES + (4 * j) / GPAD) * 16 + n;
@@ -264,6 +315,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
     if (n == 0) part[wave][j][r] = make_float2(M, s);
   }
   __syncthreads();
+  if (FILTER && threadIdx.x == 0) p.filt.cand_count[(int64_t)row * p.n_chunks + blockIdx.x] = n_kept_wg;
   if ((int)threadIdx.x < gb) {
     const int g = threadIdx.x;
     float M = -INFINITY;
@@ -282,8 +334,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
 }
 
 __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
-  const int row = blockIdx.x, lane = threadIdx.x;
-  for (int b = lane; b < kHistBins; b += 64) p.ghist[(int64_t)row * kHistBins + b] = 0;
+  const int lane = threadIdx.x;
+  int row = blockIdx.x;
+  if (p.gate.row_map) {
+    if ((int)blockIdx.x >= *p.gate.n_active) return;
+    row = p.gate.row_map[blockIdx.x];
+  }
+  if (p.ghist)
+    for (int b = lane; b < kHistBins; b += 64) p.ghist[(int64_t)row * kHistBins + b] = 0;
+  double rho = 0.0;  // max over heads of (exact softmax weight) / (sampled softmax weight)
   for (int g = 0; g < p.G; ++g) {
     const float2* pr = p.partials + ((int64_t)row * p.G + g) * p.n_chunks;
     float M = -INFINITY;
@@ -302,8 +361,16 @@ __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
       st.Z = z;
       st.invZ = (float)(1.0 / z);
       p.stats[(int64_t)row * p.G + g] = st;
+      if (p.bound) {
+        const float2 ss = p.samp_stats[(int64_t)row * p.G + g];
+        const double r = exp((double)ss.x - (double)M) / (z * (double)ss.y);
+        rho = r > rho || !(r == r) ? r : rho;
+      }
     }
   }
+  // A token the filter dropped had approximate score < tau^; its exact score is below rho * tau^
+  // (plus fp32 slack).  The candidate selection checks its threshold against this bound.
+  if (p.bound && lane == 0) p.bound[row] = (float)(rho * (double)p.samp_tau[row] * 1.001);
 }
 
 constexpr int kCombineThreads = 256;
@@ -312,7 +379,13 @@ constexpr int kMaxG = 64;
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams p) {
   __shared__ int hist[kHistBins];
   __shared__ float sM[kMaxG], sInv[kMaxG];
-  const int row = blockIdx.y, tid = threadIdx.x;
+  const int tid = threadIdx.x;
+  int row = blockIdx.y;
+  if (p.gate.row_map) {
+    if ((int)blockIdx.y >= *p.gate.n_active) return;
+    row = p.gate.row_map[blockIdx.y];
+  }
+
   const int G = p.geo.G;
   const int64_t L = p.geo.L;
   for (int b = tid; b < kHistBins; b += kCombineThreads) hist[b] = 0;
@@ -376,20 +449,31 @@ hipError_t launch_score_g(const ScoreParams& p, int gb, dim3 grid, hipStream_t s
   return hipGetLastError();
 }
 
-}  // namespace
-
-int max_group_per_launch() { return 8; }
-
-template <int D>
+template <int D, bool FILTER>
 hipError_t launch_score_mfma(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
   if (gb <= 4)
-    hipLaunchKernelGGL((score_mfma_kernel<D, 4>), grid, dim3(kScoreThreads), 0, s, p, gb);
+    hipLaunchKernelGGL((score_mfma_kernel<D, 4, FILTER>), grid, dim3(kScoreThreads), 0, s, p, gb);
   else if (gb <= 8)
-    hipLaunchKernelGGL((score_mfma_kernel<D, 8>), grid, dim3(kScoreThreads), 0, s, p, gb);
+    hipLaunchKernelGGL((score_mfma_kernel<D, 8, FILTER>), grid, dim3(kScoreThreads), 0, s, p, gb);
   else
-    hipLaunchKernelGGL((score_mfma_kernel<D, 16>), grid, dim3(kScoreThreads), 0, s, p, gb);
+    hipLaunchKernelGGL((score_mfma_kernel<D, 16, FILTER>), grid, dim3(kScoreThreads), 0, s, p, gb);
   return hipGetLastError();
 }
+
+}  // namespace
+
+// Fast path: bf16, G <= 16 (one launch covers the group).
+hipError_t launch_score_filter(const ScoreParams& p0, hipStream_t s) {
+  const int rows = p0.geo.n_problems * p0.geo.Hkv;
+  dim3 grid((unsigned)p0.n_chunks, (unsigned)rows);
+  ScoreParams p = p0;
+  p.g0 = 0;
+  if (p.geo.dtype != DT_BF16 || p.geo.G > 16) return hipErrorInvalidValue;
+  return p.geo.D == 128 ? launch_score_mfma<128, true>(p, p.geo.G, grid, s)
+                        : launch_score_mfma<64, true>(p, p.geo.G, grid, s);
+}
+
+int max_group_per_launch() { return 8; }
 
 hipError_t launch_score(const ScoreParams& p0, hipStream_t s) {
   const int rows = p0.geo.n_problems * p0.geo.Hkv;
@@ -401,7 +485,7 @@ hipError_t launch_score(const ScoreParams& p0, hipStream_t s) {
     const int gb = p0.geo.G - g0 < per_launch ? p0.geo.G - g0 : per_launch;
     hipError_t e;
     if (p.geo.dtype == DT_BF16)
-      e = p.geo.D == 128 ? launch_score_mfma<128>(p, gb, grid, s) : launch_score_mfma<64>(p, gb, grid, s);
+      e = p.geo.D == 128 ? launch_score_mfma<128, false>(p, gb, grid, s) : launch_score_mfma<64, false>(p, gb, grid, s);
     else
       e = p.geo.D == 128 ? launch_score_g<DT_F32, 128>(p, gb, grid, s) : launch_score_g<DT_F32, 64>(p, gb, grid, s);
     if (e != hipSuccess) return e;

@@ -16,108 +16,21 @@
 //      indices.
 #include "device_utils.h"
 #include "kernels.h"
+#include "radix_select.h"
 
 namespace sagekv {
 
 namespace {
 
-constexpr int kTopkThreads = 1024;
-constexpr int kTopkWaves = kTopkThreads / kWave;
-
-struct TopkShared {
-  int hist[kHistBins];
-  int wave_tot[kTopkWaves];
-  int pick_bin;
-  int pick_rem;
-};
-
-// Largest digit b such that count(digits >= b) >= k_rem; returns b and the rank left inside it.
-__device__ void pick_digit(TopkShared& sh, int nb, int k_rem, int* bin, int* rem) {
-  const int t = threadIdx.x;
-  if (t == 0) {
-    sh.pick_bin = 0;
-    sh.pick_rem = 1;
-  }
-  const int i0 = nb - 1 - 2 * t, i1 = nb - 2 - 2 * t;  // descending digits
-  const int c0 = i0 >= 0 ? sh.hist[i0] : 0;
-  const int c1 = i1 >= 0 ? sh.hist[i1] : 0;
-  int tot;
-  const int incl = block_scan_incl<kTopkThreads>(c0 + c1, sh.wave_tot, &tot);
-  const int before = incl - c0 - c1;
-  if (before < k_rem && k_rem <= before + c0) {
-    sh.pick_bin = i0;
-    sh.pick_rem = k_rem - before;
-  } else if (before + c0 < k_rem && k_rem <= incl) {
-    sh.pick_bin = i1;
-    sh.pick_rem = k_rem - before - c0;
-  }
-  __syncthreads();
-  *bin = sh.pick_bin;
-  *rem = sh.pick_rem;
-  __syncthreads();
-}
-
-__device__ void hist_pass(TopkShared& sh, const float* cand, int64_t E, uint32_t prefix, uint32_t mask, int shift,
-                          int nbits) {
-  for (int b = threadIdx.x; b < kHistBins; b += kTopkThreads) sh.hist[b] = 0;
-  __syncthreads();
-  const uint32_t dm = (1u << nbits) - 1u;
-  for (int64_t i = threadIdx.x; i < E; i += kTopkThreads) {
-    const uint32_t key = __float_as_uint(cand[i]);
-    if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dm], 1);
-  }
-  __syncthreads();
-}
-
-// k-th largest key among cand[0..E) and how many elements equal to it belong to the top k.
-// first_hist_ready: sh.hist already holds the histogram of the first digit.
-__device__ void radix_select(TopkShared& sh, const float* cand, int64_t E, int k, bool first_hist_ready,
-                             uint32_t* tau, int* quota) {
-  int bin, rem = k;
-  if (!first_hist_ready) hist_pass(sh, cand, E, 0u, 0u, 20, 11);
-  pick_digit(sh, 1 << 11, rem, &bin, &rem);
-  uint32_t prefix = (uint32_t)bin << 20;
-  hist_pass(sh, cand, E, prefix, 0xFFF00000u, 9, 11);
-  pick_digit(sh, 1 << 11, rem, &bin, &rem);
-  prefix |= (uint32_t)bin << 9;
-  hist_pass(sh, cand, E, prefix, 0xFFFFFE00u, 0, 9);
-  pick_digit(sh, 1 << 9, rem, &bin, &rem);
-  *tau = prefix | (uint32_t)bin;
-  *quota = rem;
-}
-
-template <int DT>
-__device__ double elem_f64(const void* base, int64_t i);
-template <>
-__device__ double elem_f64<DT_BF16>(const void* base, int64_t i) {
-  return (double)__uint_as_float((uint32_t)((const uint16_t*)base)[i] << 16);
-}
-template <>
-__device__ double elem_f64<DT_F32>(const void* base, int64_t i) {
-  return (double)((const float*)base)[i];
-}
-
-// Score of token `tok` of the row in fp64, rounded once to fp32.
-template <int DT>
-__device__ float refined_score(const TopkParams& p, int prob, int c, int row, int64_t tok) {
-  const int D = p.geo.D, G = p.geo.G;
-  const int64_t k_off = (int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head + tok * p.ks_token;
-  const double inv = 1.0 / sqrt((double)D);
-  double tot = 0.0;
-  for (int g = 0; g < G; ++g) {
-    const int64_t q_off = ((int64_t)prob * p.geo.Hq + c * G + g) * D;
-    double acc = 0.0;
-    for (int j = 0; j < D; ++j) acc += elem_f64<DT>(p.q_last, q_off + j) * elem_f64<DT>(p.K, k_off + j);
-    const RowStat st = p.stats[(int64_t)row * G + g];
-    tot += exp(acc * inv - (double)st.M) / st.Z;
-  }
-  return (float)tot;
-}
-
 template <int DT>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   __shared__ TopkShared sh;
-  const int row = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
+  int row = blockIdx.x;
+  if (p.gate.row_map) {
+    if ((int)blockIdx.x >= *p.gate.n_active) return;
+    row = p.gate.row_map[blockIdx.x];
+  }
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int S = p.S, W = p.W, k = p.k;
   const int64_t L = p.geo.L, E = L - S - W;
@@ -141,7 +54,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
   for (int64_t i = tid; i < E; i += kTopkThreads) {
     const float v = cand[i];
-    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p, prob, c, row, S + i);
+    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, S + i);
   }
   __syncthreads();
 

@@ -17,7 +17,7 @@ def have_gpu() -> bool:
     return torch.cuda.is_available()
 
 
-def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, V_dev=None):
+def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, V_dev=None, flags=0):
     """q [P,Hq,d], K/V [P,Hkv,L,d] host arrays (or device tensors via K_dev/V_dev).
     Returns dict of host arrays: Kc, Vc, kept, scores."""
     import torch
@@ -31,7 +31,7 @@ def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, 
     Hkv, L = Kd.shape[1], Kd.shape[2]
     n_kept = S + k + W
     cap = n_kept if cap is None else cap
-    desc = sk.select_desc(qd, Kd, Vd, S, W, k, cap)
+    desc = sk.select_desc(qd, Kd, Vd, S, W, k, cap, flags=flags)
     ws = torch.empty(max(sk.sagekv_select_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
     Kc = torch.zeros((P, Hkv, cap, d), dtype=Kd.dtype, device="cuda")
     Vc = torch.zeros((P, Hkv, cap, d), dtype=Kd.dtype, device="cuda")
@@ -40,6 +40,7 @@ def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, 
     sk.sagekv_select(desc, qd, Kd, Vd, Kc, Vc, kept, scores, ws)
     torch.cuda.synchronize()
     return {
+        "redone": sk.sagekv_select_redone_rows(desc, ws),
         "Kc": synth.torch_to_host(Kc, dtype), "Vc": synth.torch_to_host(Vc, dtype), "kept": kept.cpu().numpy(),
         "scores": None if scores is None else scores.cpu().numpy(), "Kc_dev": Kc, "Vc_dev": Vc,
     }

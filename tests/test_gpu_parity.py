@@ -20,14 +20,18 @@ def rand_case(seed, P, Hq, Hkv, d, L, dtype):
 
 
 def select_parity(ref, dtype, q, K, V, S, W, k, cap=None):
-    out = gu.gpu_select(dtype, q, K, V, S, W, k, cap)
+    """Both routes of sagekv_select against the oracle: with scores_out (dense path, scores checked
+    too) and without (pre-filtered path wherever it applies).  Returns the second run's outputs."""
     Kc, Vc, kept, s = ref.select(dtype, GROUP_SUM, q, K, V, S, W, k, cap, want_scores=True)
-    gu.check_scores(out["scores"], s[:, :, 0])
-    n_ex = gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k)
-    gu.check_gather(out, K, V, S, k, W)
-    if n_ex == 0:
-        np.testing.assert_array_equal(out["Kc"], Kc)
-        np.testing.assert_array_equal(out["Vc"], Vc)
+    for want_scores in (True, False):
+        out = gu.gpu_select(dtype, q, K, V, S, W, k, cap, want_scores=want_scores)
+        if want_scores:
+            gu.check_scores(out["scores"], s[:, :, 0])
+        n_ex = gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k)
+        gu.check_gather(out, K, V, S, k, W)
+        if n_ex == 0:
+            np.testing.assert_array_equal(out["Kc"], Kc)
+            np.testing.assert_array_equal(out["Vc"], Vc)
     return out, (Kc, Vc, kept, s)
 
 
@@ -158,11 +162,63 @@ def test_select_without_scores_out_matches(ref):
     np.testing.assert_array_equal(a["Kc"], b["Kc"])
 
 
+@pytest.mark.parametrize(
+    "Hq,Hkv,d,L,S,W,k",
+    [
+        (8, 2, 128, 40000, 4, 128, 1000),    # G=4
+        (7, 1, 128, 50021, 3, 77, 2000),     # G=7, ragged
+        (16, 2, 128, 30011, 0, 1, 500),      # G=8, no sink, window = last token
+        (24, 2, 128, 24000, 4, 64, 300),     # G=12: heads padded to 16
+        (4, 2, 64, 33000, 4, 300, 800),      # d=64, G=2
+        (3, 3, 64, 20000, 70, 400, 1),       # G=1, k=1, sink and window larger than their samples
+    ],
+)
+def test_select_prefiltered_path(ref, Hq, Hkv, d, L, S, W, k):
+    """Shapes where the pre-filtered path applies (bf16, 5k + 8192 <= E): it must certify its rows."""
+    q, K, V = rand_case(200 + Hq + d, 2, Hq, Hkv, d, L, BF16)
+    out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
+    assert out["redone"] == 0
+    dense = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=False, flags=1)
+    assert dense["redone"] == -1
+    np.testing.assert_array_equal(dense["kept"], out["kept"])
+
+
+def test_prefilter_falls_back_when_all_scores_tie(ref):
+    """q = 0: every token passes the filter, the candidate list overflows, every row is redone densely."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 30000, 4, 50, 700
+    q, K, V = rand_case(9, P, Hq, Hkv, d, L, BF16)
+    q[:] = 0
+    out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
+    assert out["redone"] == P * Hkv
+    want = list(range(S + k)) + list(range(L - W, L))
+    for c in range(Hkv):
+        assert out["kept"][0, c].tolist() == want
+
+
+@pytest.mark.parametrize("sampled", [True, False])
+def test_prefilter_with_one_token_carrying_most_of_the_mass(ref, sampled):
+    """One candidate holds ~70% of head 0's attention.  If the strided sample contains it, the
+    sample counts it ~32 times, the sampled normaliser is far too large, the bound on dropped
+    tokens exceeds the k-th score and the row must be redone densely.  If the sample misses it the
+    filter is merely more permissive and the row is certified.  Either way the result is exact."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 4, 1, 128, 40000, 4, 64, 500
+    q, K, V = rand_case(21, P, Hq, Hkv, d, L, BF16)
+    E = L - S - W
+    n_cand_s = max(1024, min(8192, E // 32))  # the library's sample size for this row
+    t = S + (7 * E) // n_cand_s + (0 if sampled else 9)
+    q64 = synth.to_f64(q[0, 0], BF16)
+    K[0, 0, t] = synth.round_to_dtype(12.0 * q64 / np.linalg.norm(q64), BF16)  # logit ~ 12
+    out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
+    assert out["redone"] == (1 if sampled else 0)
+    assert t in out["kept"][0, 0].tolist()
+
+
 def test_select_C2_shape_two_layers(ref):
     """Config C2's row shape (32q/8kv, d128, bf16, L 32768, 4+1788+256) on 2 of its 32 layers."""
     cfg = synth.CONFIGS["C2"].with_(n_layers=2)
     q, K, V, pos = synth.kv_host(cfg)
     out, _ = select_parity(ref, cfg.dtype, q, K, V, cfg.n_sink, cfg.n_recent, cfg.k)
+    assert out["redone"] == 0
     kept = out["kept"].reshape(cfg.rows, -1)
     for r in range(cfg.rows):
         assert set(pos[r].tolist()) <= set(kept[r].tolist())
