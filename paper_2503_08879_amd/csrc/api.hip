@@ -23,7 +23,9 @@ constexpr float kBand = 1.0f / 4096.0f;
 // Sizes of the fast (pre-filtered) eviction path for one descriptor; ok = the path applies.
 struct FastPlan {
   bool ok;
-  int n_sink_s, n_cand_s, n_recent_s, rank, cap, Gs;
+  int nA, nB, nC, validA, validC, rank, cap, Gs;
+  int64_t stepB;
+  float wA, wB, wC;
 };
 
 FastPlan fast_plan(const sagekv_select_desc* d) {
@@ -38,13 +40,20 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
     f.ok = false;
     return f;
   }
-  int64_t target = E / 32;
-  target = target < 1024 ? 1024 : (target > 8192 ? 8192 : target);
-  f.n_cand_s = (int)(E < target ? E : target);
-  f.n_sink_s = d->n_sink < 64 ? d->n_sink : 64;
-  f.n_recent_s = d->n_recent < 256 ? d->n_recent : 256;
+  // sample: blocks of 64 consecutive tokens, about 1/64 of the candidates (16 to 128 blocks); the
+  // sample is read from HBM on top of the full pass over K, so its share is kept small
+  int64_t nb = E / 4096;
+  f.nB = (int)(nb < 16 ? 16 : (nb > 128 ? 128 : nb));
+  f.stepB = ((E - 64) << 16) / (f.nB - 1);
+  f.nA = d->n_sink > 0 ? 1 : 0;
+  f.validA = d->n_sink < 64 ? d->n_sink : 64;
+  f.nC = d->n_recent >= 256 ? 4 : (d->n_recent + 63) / 64;
+  f.validC = d->n_recent < 64 * f.nC ? d->n_recent : 64 * f.nC;
+  f.wA = f.nA ? (float)d->n_sink / (float)f.validA : 0.f;
+  f.wB = (float)E / (float)(64 * f.nB);
+  f.wC = (float)d->n_recent / (float)f.validC;
   // threshold = sample quantile that about 1.5 k tokens of the row exceed, plus 3 sigma of its rank
-  const double r = 1.5 * (double)d->k * (double)f.n_cand_s / (double)E;
+  const double r = 1.5 * (double)d->k * (double)(64 * f.nB) / (double)E;
   f.rank = (int)ceil(r + 3.0 * sqrt(r) + 1.0);
   f.Gs = (G + 3) / 4 * 4;
   return f;
@@ -108,9 +117,9 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   l.ghist = take(rows * kHistBins * sizeof(int));
   if (l.fast.ok) {
     const FastPlan& f = l.fast;
-    const size_t ns = (size_t)f.n_sink_s + f.n_cand_s + f.n_recent_s;
-    l.samp_logit = take(rows * ns * l.G * sizeof(float));
-    l.samp_score = take(rows * f.n_cand_s * sizeof(float));
+    const size_t ns = (size_t)64 * (f.nA + f.nB + f.nC);
+    l.samp_logit = take(rows * ns * f.Gs * sizeof(float));
+    l.samp_score = take(0);
     l.samp_stats = take(rows * l.G * sizeof(float2));
     l.samp_tau = take(rows * sizeof(float));
     const size_t slots = rows * l.n_chunks * kScoreChunk;  // every token has a slot: chunks cannot overflow
@@ -338,12 +347,18 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
     mp.S = d->n_sink;
     mp.W = d->n_recent;
     mp.k = d->k;
-    mp.n_sink_s = f.n_sink_s;
-    mp.n_cand_s = f.n_cand_s;
-    mp.n_recent_s = f.n_recent_s;
+    mp.nA = f.nA;
+    mp.nB = f.nB;
+    mp.nC = f.nC;
+    mp.stepB = f.stepB;
+    mp.validA = f.validA;
+    mp.validC = f.validC;
+    mp.wA = f.wA;
+    mp.wB = f.wB;
+    mp.wC = f.wC;
     mp.rank = f.rank;
+    mp.Gs = f.Gs;
     mp.samp_logit = (float*)(ws + l.samp_logit);
-    mp.samp_score = (float*)(ws + l.samp_score);
     mp.samp_stats = samp_stats;
     mp.samp_tau = samp_tau;
     mp.row_fail = row_fail;

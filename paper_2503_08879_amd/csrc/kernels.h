@@ -98,21 +98,36 @@ struct TopkParams {
   float band;  // relative half-width of the fp64 re-evaluation band around the k-th score
 };
 
+// The sample of the fast path: blocks of 64 consecutive tokens (one wave-block of the MFMA score
+// kernel each): the first block of the row if there is a sink, nB blocks spread evenly over the
+// eviction candidates, nC blocks at the end of the recent window.
 struct SampleParams {
   RowGeom geo;
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;
   int S, W, k;
-  int n_sink_s, n_cand_s, n_recent_s;  // sample sizes of the three parts of the row
-  int rank;                            // rank (1-based) of the threshold among the sampled candidates
-  float* samp_logit;                   // [rows][n_samp][G] scratch
-  float* samp_score;                   // [rows][n_cand_s] scratch
-  float2* samp_stats;                  // out [rows][G]
-  float* samp_tau;                     // out [rows]
-  int* row_fail;                       // out [rows] = 0
+  int nA, nB, nC;       // blocks per part
+  int64_t stepB;        // 48.16 fixed-point distance between the starts of candidate blocks
+  int validA, validC;   // sink tokens in block A; recent tokens covered by the C blocks
+  float wA, wB, wC;     // tokens of the row one sampled token stands for
+  int rank;             // rank (1-based) of the threshold among the 64 * nB sampled candidates
+  int Gs;               // heads per token in samp_logit (G rounded up to a multiple of 4)
+  float* samp_logit;    // [rows][64 * (nA + nB + nC)][Gs] scratch
+  float2* samp_stats;   // out [rows][G]
+  float* samp_tau;      // out [rows]
+  int* row_fail;        // out [rows] = 0
   float scale;
 };
+
+// First token of sample block b.
+__host__ __device__ inline int64_t sample_block_start(const SampleParams& p, int b) {
+  if (b < p.nA) return 0;
+  b -= p.nA;
+  if (b < p.nB) return p.S + (((int64_t)b * p.stepB) >> 16);
+  b -= p.nB;
+  return p.geo.L - 64 * (int64_t)(p.nC - b);
+}
 
 // Final selection of the fast path, on the candidate list of each row.
 struct TopkCandParams {
@@ -162,7 +177,8 @@ struct DecodeParams {
   float scale;
 };
 
-hipError_t launch_sample(const SampleParams& p, hipStream_t s);
+hipError_t launch_sample(const SampleParams& p, hipStream_t s);         // logits + statistics
+hipError_t launch_sample_logits(const SampleParams& p, hipStream_t s);
 hipError_t launch_score_filter(const ScoreParams& p, hipStream_t s);
 hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s);
 hipError_t launch_collect_failed(const int* row_fail, int rows, int* fail_list, int* n_fail, hipStream_t s);

@@ -2,7 +2,7 @@
 // every token's logits during the K stream and reading them back, keep only the few tokens that
 // can reach the top-k.
 //
-//   sample_kernel     a strided sample of each row -> approximate softmax statistics (M^, Z^) per
+//   sample_*_kernel   a strided sample of each row -> approximate softmax statistics (M^, Z^) per
 //                     head and a conservative threshold tau^ on the approximate score: the sample
 //                     quantile of rank ~1.5 k/E, so about 1.5 k tokens of the row pass it.
 //   (score pass)      score_mfma_kernel<FILTER>: exact logits, exact softmax partials; tokens
@@ -10,9 +10,9 @@
 //                     in the slots of their score chunk (no global atomics).
 //   (stats)           exact (M, Z) per head and the bound rho * tau^ on the exact score of every
 //                     token that was dropped.
-//   topk_cand_kernel  exact scores of the candidates, radix select, fp64 re-evaluation near the
-//                     k-th score, exact select, then an LDS bitmap turns the unordered list into
-//                     ascending positions.  The row is only accepted if its k-th score clears the
+//   topk_cand_kernel  exact scores of the candidates, radix select of the k-th score, fp64
+//                     re-evaluation and exact ranking of the few candidates around it, then an LDS
+//                     bitmap turns the unordered selection into ascending positions.  The row is only accepted if its k-th score clears the
 //                     bound, i.e. if no dropped token could have been selected; otherwise the row
 //                     is flagged and the dense path redoes it.
 #include "device_utils.h"
@@ -23,110 +23,83 @@ namespace sagekv {
 
 namespace {
 
-constexpr int kMaxTies = 1024;
+constexpr int kMaxBand = 1024;  // candidates re-scored in fp64 per row on the fast path
 constexpr int kFastMaxG = 16;
 
-__device__ inline float block_max(float v, float* red) {
-  v = wave_max(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = red[0];
-#pragma unroll
-  for (int i = 1; i < kTopkWaves; ++i) r = fmaxf(r, red[i]);
-  return r;
-}
-
-__device__ inline float block_sum(float v, float* red) {
-  v = group_sum<64>(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float r = 0.f;
-#pragma unroll
-  for (int i = 0; i < kTopkWaves; ++i) r += red[i];
-  return r;
-}
-
-template <int D>
-__global__ __launch_bounds__(kTopkThreads) void sample_kernel(SampleParams p) {
-  constexpr int CH = D / 8, TPL = 64 / CH, U = 8;
+// Per row: approximate softmax statistics from the sampled logits, approximate scores of the
+// sampled candidates, and their rank-th largest value = the row's filter threshold.
+__global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams p) {
   __shared__ TopkShared sh;
-  __shared__ float red[kTopkWaves];
+  __shared__ float2 red[kTopkWaves][kFastMaxG];
   __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
+  __shared__ float ss[8192];  // approximate scores of the sampled candidates
 
   const int row = blockIdx.x, tid = threadIdx.x;
-  const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int lane = tid & 63, wave = tid >> 6;
-  const int tq = lane / CH, cl = lane % CH;
-  const int G = p.geo.G;
-  const int64_t L = p.geo.L, S = p.S, W = p.W, E = L - S - W;
-  const int nA = p.n_sink_s, nB = p.n_cand_s, nC = p.n_recent_s, ns = nA + nB + nC;
-
+  const int G = p.geo.G, Gs = p.Gs;
+  const int n_slots = 64 * (p.nA + p.nB + p.nC), nB = 64 * p.nB;
+  const float* slog = p.samp_logit + (int64_t)row * n_slots * Gs;
   if (tid == 0) p.row_fail[row] = 0;
 
-  auto sample_token = [&](int j) -> int64_t {
-    if (j < nA) return (int64_t)j * S / nA;
-    j -= nA;
-    if (j < nB) return S + (int64_t)j * E / nB;
-    j -= nB;
-    return L - W + (int64_t)j * W / nC;
-  };
-  auto sample_weight = [&](int j) -> float {
-    if (j < nA) return (float)S / (float)nA;
-    if (j < nA + nB) return (float)E / (float)nB;
-    return (float)W / (float)nC;
+  // weight of sample slot s (0 = the slot is outside the part its block samples)
+  auto weight = [&](int s) -> float {
+    const int b = s >> 6, t = s & 63;
+    if (b < p.nA) return t < p.validA ? p.wA : 0.f;
+    if (b < p.nA + p.nB) return p.wB;
+    return 64 * (p.nA + p.nB + p.nC) - s <= p.validC ? p.wC : 0.f;
   };
 
-  // 1. logits of the sampled tokens
-  const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
-  const char* qrow = (const char*)p.q_last + ((int64_t)prob * p.geo.Hq + (int64_t)c * G) * D * 2;
-  float* slog = p.samp_logit + (int64_t)row * ns * G;
-  for (int j0 = wave * TPL * U; j0 < ns; j0 += kTopkWaves * TPL * U) {
-    uint4 kv[U];
+  // approximate softmax statistics per head, one pass: M^ = max, Z^ = sum of weight * exp(l - M^)
+  {
+    float m[kFastMaxG], z[kFastMaxG];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      int j = j0 + u * TPL + tq;
-      j = j < ns ? j : ns - 1;
-      kv[u] = ld16(Krow + sample_token(j) * p.ks_token * 2 + cl * 16);
+    for (int g = 0; g < kFastMaxG; ++g) {
+      m[g] = -INFINITY;
+      z[g] = 0.f;
     }
-    for (int g = 0; g < G; ++g) {
-      const uint4 qv = ld16(qrow + ((int64_t)g * D + cl * 8) * 2);
+    for (int s = tid; s < n_slots; s += kTopkThreads) {
+      const float w = weight(s);
+      if (w > 0.f) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float v = group_sum<CH>(dot16<DT_BF16>(kv[u], qv, 0.f)) * p.scale;
-        const int j = j0 + u * TPL + tq;
-        if (j < ns && cl == 0) slog[(int64_t)j * G + g] = v;
+        for (int g = 0; g < kFastMaxG; ++g)
+          if (g < G) {
+            const float x = slog[(int64_t)s * Gs + g];
+            const float mn = fmaxf(m[g], x);
+            z[g] = z[g] * exp_fast(m[g] - mn) + w * exp_fast(x - mn);
+            m[g] = mn;
+          }
       }
     }
-  }
-  __syncthreads();
-
-  // 2. approximate softmax statistics per head: M^ = max, Z^ = sum of weight * exp(l - M^)
-  for (int g = 0; g < G; ++g) {
-    float mx = -INFINITY;
-    for (int j = tid; j < ns; j += kTopkThreads) mx = fmaxf(mx, slog[(int64_t)j * G + g]);
-    mx = block_max(mx, red);
-    float z = 0.f;
-    for (int j = tid; j < ns; j += kTopkThreads) z += sample_weight(j) * exp_fast(slog[(int64_t)j * G + g] - mx);
-    z = block_sum(z, red);
-    if (tid == 0) {
-      sM[g] = mx;
-      sInv[g] = 1.0f / z;
-      p.samp_stats[(int64_t)row * G + g] = make_float2(mx, 1.0f / z);
+#pragma unroll
+    for (int g = 0; g < kFastMaxG; ++g)
+      if (g < G) {
+        const float M = wave_max(m[g]);
+        float zz = (m[g] == -INFINITY) ? 0.f : z[g] * exp_fast(m[g] - M);
+        zz = group_sum<64>(zz);
+        if (lane == 0) red[wave][g] = make_float2(M, zz);
+      }
+    __syncthreads();
+    if (tid < G) {
+      float M = red[0][tid].x;
+      for (int w = 1; w < kTopkWaves; ++w) M = fmaxf(M, red[w][tid].x);
+      float zz = 0.f;
+      for (int w = 0; w < kTopkWaves; ++w)
+        zz += (red[w][tid].x == -INFINITY) ? 0.f : red[w][tid].y * exp_fast(red[w][tid].x - M);
+      sM[tid] = M;
+      sInv[tid] = 1.0f / zz;
+      p.samp_stats[(int64_t)row * G + tid] = make_float2(M, 1.0f / zz);
     }
   }
   __syncthreads();
 
-  // 3. approximate scores of the sampled candidates, 4. their rank-th largest value
-  float* ss = p.samp_score + (int64_t)row * nB;
-  for (int j = tid; j < nB; j += kTopkThreads) {
+  for (int s = tid; s < nB; s += kTopkThreads) {
+    const float* lg = slog + (int64_t)(64 * p.nA + s) * Gs;
     float a = 0.f;
-    for (int g = 0; g < G; ++g) a += exp_fast(slog[(int64_t)(nA + j) * G + g] - sM[g]) * sInv[g];
-    ss[j] = a;
+    for (int g = 0; g < G; ++g) a += exp_fast(lg[g] - sM[g]) * sInv[g];
+    ss[s] = a;
   }
   __syncthreads();
-  float tau_f = 0.f;  // rank beyond the sample: everything passes (the row then overflows and is redone)
+  float tau_f = 0.f;  // rank beyond the sample: everything passes (the row is then redone densely)
   if (p.rank >= 1 && p.rank <= nB) {
     uint32_t tau;
     int quota;
@@ -140,8 +113,9 @@ template <int DT>
 __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams p) {
   __shared__ TopkShared sh;
   __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
-  __shared__ int tie_idx[kMaxTies];
-  __shared__ int n_tie;
+  __shared__ int band_j[kMaxBand], band_tok[kMaxBand];
+  __shared__ float band_v[kMaxBand];
+  __shared__ int n_band, n_above;
   extern __shared__ uint32_t bitmap[];  // one bit per eviction candidate of the row
 
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -170,7 +144,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
     sM[tid] = st.M;
     sInv[tid] = st.invZ;
   }
-  if (tid == 0) n_tie = 0;
+  if (tid == 0) n_band = n_above = 0;
   __syncthreads();
   const int n_c = chunk_off[p.n_chunks];
   if (n_c > p.cap || n_c < k) {  // far more candidates than planned, or the threshold was too high
@@ -178,67 +152,103 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
     return;
   }
 
-  // exact fp32 scores of the candidates (same arithmetic and order as the dense combine stage);
-  // one wave per chunk
+  // exact fp32 scores of the candidates (same arithmetic and order as the dense combine stage)
   float* cs = p.cand_score + (int64_t)row * p.cap;
   int32_t* ci = p.cand_pos + (int64_t)row * p.cap;
-  for (int ch = tid >> 6; ch < p.n_chunks; ch += kTopkWaves) {
-    const int n = chunk_off[ch + 1] - chunk_off[ch];
-    const int64_t slot = ((int64_t)row * p.n_chunks + ch) * kScoreChunk;
-    for (int j = tid & 63; j < n; j += 64) {
-      const float* lg = p.cand_logit + (slot + j) * p.Gs;
-      float a = 0.f;
-      for (int g = 0; g < G; ++g) a += exp_accurate(lg[g] - sM[g]) * sInv[g];
-      cs[chunk_off[ch] + j] = a;
-      ci[chunk_off[ch] + j] = p.cand_idx[slot + j];
+  for (int d0 = 0; d0 < n_c; d0 += 4 * kTopkThreads) {
+    int64_t slot[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // independent lookups: their loads overlap
+      const int dj = d0 + u * kTopkThreads + tid;
+      int lo_c = 0, hi_c = p.n_chunks;  // chunk with chunk_off[ch] <= dj < chunk_off[ch + 1]
+      while (hi_c - lo_c > 1) {
+        const int mid = (lo_c + hi_c) >> 1;
+        if (chunk_off[mid] <= dj) lo_c = mid; else hi_c = mid;
+      }
+      slot[u] = dj < n_c ? ((int64_t)row * p.n_chunks + lo_c) * kScoreChunk + (dj - chunk_off[lo_c]) : -1;
+    }
+    float4 lg[4][kFastMaxG / 4];
+    int32_t ti[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t sl = slot[u] < 0 ? (int64_t)row * p.n_chunks * kScoreChunk : slot[u];
+      ti[u] = p.cand_idx[sl];
+#pragma unroll
+      for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
+        if (g4 * 4 < G) lg[u][g4] = *reinterpret_cast<const float4*>(p.cand_logit + sl * p.Gs + g4 * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int dj = d0 + u * kTopkThreads + tid;
+      if (dj < n_c) {
+        float a = 0.f;
+#pragma unroll
+        for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
+          if (g4 * 4 < G) {
+            const float x[4] = {lg[u][g4].x, lg[u][g4].y, lg[u][g4].z, lg[u][g4].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (g4 * 4 + e < G) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
+          }
+        cs[dj] = a;
+        ci[dj] = ti[u];
+      }
     }
   }
   __syncthreads();
 
+  // coarse k-th score, then the candidates within the band around it are re-scored in fp64 and
+  // ranked exactly (score descending, index ascending); everything above the band is selected
   uint32_t tau;
   int quota;
   radix_select(sh, cs, n_c, k, false, &tau, &quota);
   const float tf = __uint_as_float(tau);
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
-  for (int j = tid; j < n_c; j += kTopkThreads) {
-    const float v = cs[j];
-    if (v >= lo && v <= hi)
-      cs[j] = refined_score<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, ci[j]);
-  }
-  __syncthreads();
-  radix_select(sh, cs, n_c, k, false, &tau, &quota);
-
-  // every token outside the list scores below bound[row]: accept only if neither the k-th score
-  // nor anything in its re-evaluation band could be such a token
-  if (!(__uint_as_float(tau) * (1.0f - 2.0f * p.band) > p.bound[row])) {
+  // every token outside the list scores below bound[row]: the row is certified only if no such
+  // token can reach the band
+  if (!(lo * (1.0f - p.band) > p.bound[row])) {
     if (tid == 0) p.row_fail[row] = 1;
     return;
   }
-
   const int n_words = (int)((E + 31) / 32);
   for (int w = tid; w < n_words; w += kTopkThreads) bitmap[w] = 0u;
   __syncthreads();
-  for (int j = tid; j < n_c; j += kTopkThreads) {
-    const uint32_t key = __float_as_uint(cs[j]);
-    const int pos = ci[j] - S;
-    if (key > tau) {
+  for (int j0 = 0; j0 < n_c; j0 += kTopkThreads) {
+    const int j = j0 + tid;
+    const float v = j < n_c ? cs[j] : 0.f;
+    const bool above = j < n_c && v > hi;
+    if (above) {
+      const int pos = ci[j] - S;
       atomicOr(&bitmap[pos >> 5], 1u << (pos & 31));
-    } else if (key == tau) {
-      const int t = atomicAdd(&n_tie, 1);
-      if (t < kMaxTies) tie_idx[t] = pos;
+    } else if (j < n_c && v >= lo) {
+      const int t = atomicAdd(&n_band, 1);
+      if (t < kMaxBand) band_j[t] = j;
     }
+    const unsigned long long bal = __ballot(above);
+    if ((tid & 63) == 0 && bal) atomicAdd(&n_above, __popcll(bal));
   }
   __syncthreads();
-  const int nt = n_tie;
-  if (nt > kMaxTies) {  // a degenerate row of equal scores: leave it to the dense path
+  const int nb = n_band, r = k - n_above;
+  if (nb > kMaxBand || r < 1 || r > nb) {  // a degenerate row of (nearly) equal scores: dense path
     if (tid == 0) p.row_fail[row] = 1;
     return;
   }
-  for (int t = tid; t < nt; t += kTopkThreads) {  // ties go to the lowest indices
-    const int me = tie_idx[t];
+  for (int t = tid >> 6; t < nb; t += kTopkWaves) {
+    const int tok = ci[band_j[t]];
+    const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c,
+                                           row, tok);
+    if ((tid & 63) == 0) {
+      band_v[t] = v;
+      band_tok[t] = tok;
+    }
+  }
+  __syncthreads();
+  for (int t = tid; t < nb; t += kTopkThreads) {
+    const float v = band_v[t];
+    const int tok = band_tok[t];
     int rank = 0;
-    for (int u = 0; u < nt; ++u) rank += tie_idx[u] < me;
-    if (rank < quota) atomicOr(&bitmap[me >> 5], 1u << (me & 31));
+    for (int u = 0; u < nb; ++u) rank += band_v[u] > v || (band_v[u] == v && band_tok[u] < tok);
+    if (rank < r) atomicOr(&bitmap[(tok - S) >> 5], 1u << ((tok - S) & 31));
   }
   __syncthreads();
 
@@ -279,11 +289,10 @@ __global__ __launch_bounds__(kTopkThreads) void collect_failed_kernel(const int*
 
 hipError_t launch_sample(const SampleParams& p, hipStream_t s) {
   const int rows = p.geo.n_problems * p.geo.Hkv;
-  if (p.geo.dtype != DT_BF16 || p.geo.G > kFastMaxG) return hipErrorInvalidValue;
-  if (p.geo.D == 128)
-    hipLaunchKernelGGL(sample_kernel<128>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
-  else
-    hipLaunchKernelGGL(sample_kernel<64>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
+  if (p.geo.dtype != DT_BF16 || p.geo.G > kFastMaxG || p.nB * 64 > 8192) return hipErrorInvalidValue;
+  hipError_t e = launch_sample_logits(p, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(sample_stats_kernel, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
   return hipGetLastError();
 }
 

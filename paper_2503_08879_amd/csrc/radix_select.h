@@ -102,4 +102,26 @@ __device__ inline float refined_score(const RowGeom& geo, const void* q_last, co
   return (float)tot;
 }
 
+// The same value computed by one whole wave: lanes split head_dim, fp64 tree reduction (the fp64
+// sum order differs from the sequential one by ~1e-16 relative, far below fp32 rounding).
+template <int DT>
+__device__ inline float refined_score_wave(const RowGeom& geo, const void* q_last, const void* K, int64_t ks_problem,
+                                        int64_t ks_head, int64_t ks_token, const RowStat* stats, int prob, int c,
+                                        int row, int64_t tok) {
+  const int D = geo.D, G = geo.G, lane = threadIdx.x & 63;
+  const int64_t k_off = (int64_t)prob * ks_problem + (int64_t)c * ks_head + tok * ks_token;
+  const double inv = 1.0 / sqrt((double)D);
+  double tot = 0.0;
+  for (int g = 0; g < G; ++g) {
+    const int64_t q_off = ((int64_t)prob * geo.Hq + c * G + g) * D;
+    double acc = 0.0;
+    for (int j = lane; j < D; j += 64) acc += elem_f64<DT>(q_last, q_off + j) * elem_f64<DT>(K, k_off + j);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
+    const RowStat st = stats[(int64_t)row * G + g];
+    tot += exp(acc * inv - (double)st.M) / st.Z;
+  }
+  return (float)tot;
+}
+
 }  // namespace sagekv

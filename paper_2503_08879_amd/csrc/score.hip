@@ -333,6 +333,74 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
   }
 }
 
+// Logits of the sampled blocks (fast path), same MFMA scheme as score_mfma_kernel: one wave per
+// 64-token block, logits to samp_logit[row][slot][Gs] (16 bytes per lane).
+template <int D, int GPAD>
+__global__ __launch_bounds__(kScoreThreads) void sample_logits_kernel(SampleParams p) {
+  constexpr int CH = D / 8, TPL = 64 / CH, NLOAD = 64 / TPL, KSTEPS = D / 32;
+  constexpr int TILES = 16 / GPAD, NACC = 4 / TILES;
+  __shared__ uint4 lds[kScoreWaves][64 * CH];
+
+  const int row = blockIdx.y;
+  const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tq = lane / CH, cl = lane % CH;
+  const int n = lane & 15, j = lane >> 4;
+  const int64_t L = p.geo.L;
+  const int G = p.geo.G;
+  const int blk = blockIdx.x * kScoreWaves + wave;
+  if (blk >= p.nA + p.nB + p.nC) return;  // wave-uniform; no workgroup barrier below
+  uint4* buf = lds[wave];
+  const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
+  const int64_t tok_bytes = p.ks_token * 2;
+  const int64_t tok_base = sample_block_start(p, blk);
+
+  uint4 kv[NLOAD];
+#pragma unroll
+  for (int i = 0; i < NLOAD; ++i) {
+    int64_t tok = tok_base + i * TPL + tq;
+    tok = tok < 0 ? 0 : (tok < L ? tok : L - 1);
+    kv[i] = ld16(Krow + tok * tok_bytes + cl * 16);
+  }
+  const int my_head = n % GPAD, my_slot = n / GPAD;
+  uint4 qa[KSTEPS];
+#pragma unroll
+  for (int kc = 0; kc < KSTEPS; ++kc) {
+    qa[kc] = make_uint4(0u, 0u, 0u, 0u);
+    if (my_head < G) {
+      const int h = c * G + my_head;
+      qa[kc] = ld16((const char*)p.q_last + (((int64_t)prob * p.geo.Hq + h) * D + (4 * kc + j) * 8) * 2);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NLOAD; ++i) {
+    const int t = i * TPL + tq;
+    buf[t * CH + (cl ^ (t & (CH - 1)))] = kv[i];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  const int hbase = (4 * j) % GPAD;
+  float* out = p.samp_logit + ((int64_t)row * (p.nA + p.nB + p.nC) + blk) * 64 * p.Gs;
+#pragma unroll
+  for (int a = 0; a < NACC; ++a) {
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ts = 0; ts < TILES; ++ts) {
+      const int t = (a * TILES + ts) * 16 + n;
+#pragma unroll
+      for (int kc = 0; kc < KSTEPS; ++kc) {
+        const uint4 b = buf[t * CH + ((4 * kc + j) ^ (n & (CH - 1)))];
+        const uint4 qv = (my_slot == ts) ? qa[kc] : make_uint4(0u, 0u, 0u, 0u);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qv), __builtin_bit_cast(bf16x8_t, b),
+                                                      acc, 0, 0, 0);
+      }
+    }
+    const int t_local = (a * TILES + (4 * j) / GPAD) * 16 + n;
+    if (hbase < p.Gs)
+      *reinterpret_cast<float4*>(out + (int64_t)t_local * p.Gs + hbase) =
+          make_float4(acc[0] * p.scale, acc[1] * p.scale, acc[2] * p.scale, acc[3] * p.scale);
+  }
+}
+
 __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
   const int lane = threadIdx.x;
   int row = blockIdx.x;
@@ -471,6 +539,21 @@ hipError_t launch_score_filter(const ScoreParams& p0, hipStream_t s) {
   if (p.geo.dtype != DT_BF16 || p.geo.G > 16) return hipErrorInvalidValue;
   return p.geo.D == 128 ? launch_score_mfma<128, true>(p, p.geo.G, grid, s)
                         : launch_score_mfma<64, true>(p, p.geo.G, grid, s);
+}
+
+hipError_t launch_sample_logits(const SampleParams& p, hipStream_t s) {
+  const int rows = p.geo.n_problems * p.geo.Hkv;
+  const int nb = p.nA + p.nB + p.nC;
+  if (p.geo.dtype != DT_BF16 || p.geo.G > 16) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((nb + kScoreWaves - 1) / kScoreWaves), (unsigned)rows);
+#define SAGEKV_LAUNCH(DD, GP) hipLaunchKernelGGL((sample_logits_kernel<DD, GP>), grid, dim3(kScoreThreads), 0, s, p)
+  if (p.geo.D == 128) {
+    if (p.geo.G <= 4) SAGEKV_LAUNCH(128, 4); else if (p.geo.G <= 8) SAGEKV_LAUNCH(128, 8); else SAGEKV_LAUNCH(128, 16);
+  } else {
+    if (p.geo.G <= 4) SAGEKV_LAUNCH(64, 4); else if (p.geo.G <= 8) SAGEKV_LAUNCH(64, 8); else SAGEKV_LAUNCH(64, 16);
+  }
+#undef SAGEKV_LAUNCH
+  return hipGetLastError();
 }
 
 int max_group_per_launch() { return 8; }

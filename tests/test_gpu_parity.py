@@ -198,14 +198,15 @@ def test_prefilter_falls_back_when_all_scores_tie(ref):
 @pytest.mark.parametrize("sampled", [True, False])
 def test_prefilter_with_one_token_carrying_most_of_the_mass(ref, sampled):
     """One candidate holds ~70% of head 0's attention.  If the strided sample contains it, the
-    sample counts it ~32 times, the sampled normaliser is far too large, the bound on dropped
+    sample counts it ~40 times, the sampled normaliser is far too large, the bound on dropped
     tokens exceeds the k-th score and the row must be redone densely.  If the sample misses it the
     filter is merely more permissive and the row is certified.  Either way the result is exact."""
     P, Hq, Hkv, d, L, S, W, k = 1, 4, 1, 128, 40000, 4, 64, 500
     q, K, V = rand_case(21, P, Hq, Hkv, d, L, BF16)
     E = L - S - W
-    n_cand_s = max(1024, min(8192, E // 32))  # the library's sample size for this row
-    t = S + (7 * E) // n_cand_s + (0 if sampled else 9)
+    n_blocks = max(16, min(128, E // 4096))  # the library samples this many 64-token blocks of candidates
+    start7 = S + ((7 * (((E - 64) << 16) // (n_blocks - 1))) >> 16)
+    t = start7 + 5 + (0 if sampled else 1200)  # inside sample block 7, or between blocks 7 and 8
     q64 = synth.to_f64(q[0, 0], BF16)
     K[0, 0, t] = synth.round_to_dtype(12.0 * q64 / np.linalg.norm(q64), BF16)  # logit ~ 12
     out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
