@@ -46,8 +46,9 @@ def read_traffic(cfg_name):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(cfg, n_layers, n_decode):
-    """Times the CPU oracle, as it stands, on the first n_layers layers of the same workload."""
+def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
+    """Times the CPU oracle, as it stands, on the first n_layers layers of the same workload: the
+    eviction pass repeated for about select_seconds, then decode steps for about decode_seconds."""
     import numpy as np
 
     import synth
@@ -59,31 +60,35 @@ def cpu_baseline(cfg, n_layers, n_decode):
     shp = (sub.n_problems, sub.n_kv_heads, sub.L, sub.head_dim)
     K = np.stack([synth.kv_row_host(sub, "K", r, pos, nrows) for r in range(sub.rows)]).reshape(shp)
     V = np.stack([synth.kv_row_host(sub, "V", r) for r in range(sub.rows)]).reshape(shp)
-    t0 = time.perf_counter()
-    Kc, Vc, kept = ref.select(sub.dtype, ref.GROUP_SUM, q, K, V, sub.n_sink, sub.n_recent, sub.k)
-    t_sel = time.perf_counter() - t0
-    t_dec = 0.0
-    P, d = cfg.n_problems, cfg.head_dim
-    for t in range(n_decode):
-        qs, kn, vn = synth.decode_inputs_host(cfg, t)
+    t_sel, n_sel = 0.0, 0
+    while t_sel < select_seconds:
+        t0 = time.perf_counter()
+        Kc, Vc, kept = ref.select(sub.dtype, ref.GROUP_SUM, q, K, V, sub.n_sink, sub.n_recent, sub.k)
+        t_sel += time.perf_counter() - t0
+        n_sel += 1
+    t_dec, n_dec = 0.0, 0
+    while t_dec < decode_seconds:
+        qs, kn, vn = synth.decode_inputs_host(cfg, n_dec % max(cfg.decode_steps, 1))
         qs, kn, vn = (np.ascontiguousarray(x[: sub.n_problems]) for x in (qs, kn, vn))
         t0 = time.perf_counter()
         ref.append(sub.dtype, Kc, Vc, kn, vn, sub.n_sink + sub.k, sub.n_recent)
         ref.decode_attn(sub.dtype, ref.GROUP_SUM, qs, Kc, Vc, sub.budget)
         t_dec += time.perf_counter() - t0
+        n_dec += 1
     sel_b, dec_b, _ = algorithmic_bytes(sub)
-    total_b = sel_b + n_decode * dec_b
+    # same mix as a bench step: one eviction pass + cfg.decode_steps decode steps
+    t_step = t_sel / n_sel + cfg.decode_steps * t_dec / n_dec
     return {
-        "value": total_b / (t_sel + t_dec) / 1e9,
+        "value": (sel_b + cfg.decode_steps * dec_b) / t_step / 1e9,
         "unit": "GB/s",
         "cores": ref.threads(),
         "kind": "oracle",
-        "sample": f"first {n_layers} of {cfg.n_layers} layers ({sub.rows} rows of L={cfg.L}): 1 eviction pass + "
-                  f"{n_decode} decode steps",
-        "select_GBps": sel_b / t_sel / 1e9,
-        "select_s": t_sel,
-        "decode_tokens_per_s": (n_decode * cfg.batch / t_dec) * (n_layers / cfg.n_layers) if t_dec > 0 else None,
-        "decode_s": t_dec,
+        "sample": f"first {n_layers} of {cfg.n_layers} layers ({sub.rows} rows of L={cfg.L}): eviction pass x{n_sel} "
+                  f"({t_sel:.1f} s), {n_dec} decode steps ({t_dec:.1f} s); value = bytes of (1 pass + "
+                  f"{cfg.decode_steps} steps) on these layers / their time",
+        "select_GBps": sel_b / (t_sel / n_sel) / 1e9,
+        "select_ms_all_layers": t_sel / n_sel * 1e3 * cfg.n_layers / n_layers,
+        "decode_tokens_per_s": cfg.batch / (t_dec / n_dec) * n_layers / cfg.n_layers,
     }, kept
 
 
@@ -96,7 +101,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per step (default: the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=2)
-    ap.add_argument("--cpu-decode-steps", type=int, default=8)
+    ap.add_argument("--cpu-select-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-decode-seconds", type=float, default=5.0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (rows are independent; no collectives are built). "
@@ -213,7 +219,7 @@ def main():
                      "algorithmic_bytes": score_b, "traffic": read_traffic(cfg.name)},
     }
     if not args.no_cpu_baseline:
-        base, kept_ref = cpu_baseline(cfg, args.cpu_layers, args.cpu_decode_steps)
+        base, kept_ref = cpu_baseline(cfg, args.cpu_layers, args.cpu_select_seconds, args.cpu_decode_seconds)
         # free check: the sampled layers' kept sets must be the oracle's
         sk.sagekv_select(sdesc, q_last, K, V, Kc, Vc, kept, None, sws)
         torch.cuda.synchronize()

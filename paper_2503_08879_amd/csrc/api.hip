@@ -40,11 +40,11 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
     f.ok = false;
     return f;
   }
-  // sample: blocks of 64 consecutive tokens, about 1/64 of the candidates (16 to 128 blocks); the
+  // sample: runs of 16 consecutive tokens, about 1/64 of the candidates (64 to 512 runs); the
   // sample is read from HBM on top of the full pass over K, so its share is kept small
   int64_t nb = E / 4096;
   f.nB = (int)(nb < 16 ? 16 : (nb > 128 ? 128 : nb));
-  f.stepB = ((E - 64) << 16) / (f.nB - 1);
+  f.stepB = ((E - 16) << 16) / (4 * f.nB - 1);  // between 16-token runs
   f.nA = d->n_sink > 0 ? 1 : 0;
   f.validA = d->n_sink < 64 ? d->n_sink : 64;
   f.nC = d->n_recent >= 256 ? 4 : (d->n_recent + 63) / 64;
@@ -52,9 +52,13 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   f.wA = f.nA ? (float)d->n_sink / (float)f.validA : 0.f;
   f.wB = (float)E / (float)(64 * f.nB);
   f.wC = (float)d->n_recent / (float)f.validC;
-  // threshold = sample quantile that about 1.5 k tokens of the row exceed, plus 3 sigma of its rank
-  const double r = 1.5 * (double)d->k * (double)(64 * f.nB) / (double)E;
-  f.rank = (int)ceil(r + 3.0 * sqrt(r) + 1.0);
+  // Threshold = the rank-th largest approximate score among the n sampled candidates.  About
+  // rank * E / n tokens of the row exceed it, with relative sigma 1/sqrt(rank); the rank is the
+  // smallest whose 4-sigma low side still keeps 1.15 k tokens (15 % covers the error of the
+  // sampled softmax normalisers): rank - 4 sqrt(rank) >= 1.15 k n / E.
+  const double r0 = 1.15 * (double)d->k * (double)(64 * f.nB) / (double)E;
+  const double x = 2.0 + sqrt(4.0 + r0);
+  f.rank = (int)ceil(x * x);
   f.Gs = (G + 3) / 4 * 4;
   return f;
 }

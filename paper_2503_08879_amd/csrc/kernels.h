@@ -98,9 +98,10 @@ struct TopkParams {
   float band;  // relative half-width of the fp64 re-evaluation band around the k-th score
 };
 
-// The sample of the fast path: blocks of 64 consecutive tokens (one wave-block of the MFMA score
-// kernel each): the first block of the row if there is a sink, nB blocks spread evenly over the
-// eviction candidates, nC blocks at the end of the recent window.
+// The sample of the fast path, in blocks of 64 tokens (one wave-block of the MFMA kernels each):
+// the first block of the row if there is a sink, nB blocks over the eviction candidates, each made
+// of four runs of 16 consecutive tokens (4 * nB runs spread evenly), nC blocks at the end of the
+// recent window.
 struct SampleParams {
   RowGeom geo;
   const void* q_last;
@@ -108,7 +109,7 @@ struct SampleParams {
   int64_t ks_problem, ks_head, ks_token;
   int S, W, k;
   int nA, nB, nC;       // blocks per part
-  int64_t stepB;        // 48.16 fixed-point distance between the starts of candidate blocks
+  int64_t stepB;        // 48.16 fixed-point distance between the starts of the 16-token candidate runs
   int validA, validC;   // sink tokens in block A; recent tokens covered by the C blocks
   float wA, wB, wC;     // tokens of the row one sampled token stands for
   int rank;             // rank (1-based) of the threshold among the 64 * nB sampled candidates
@@ -120,13 +121,14 @@ struct SampleParams {
   float scale;
 };
 
-// First token of sample block b.
-__host__ __device__ inline int64_t sample_block_start(const SampleParams& p, int b) {
-  if (b < p.nA) return 0;
+// Token sampled by slot t (0..63) of sample block b (may lie outside [0, L) for the C blocks of a
+// short row: the caller clamps).
+__host__ __device__ inline int64_t sample_token(const SampleParams& p, int b, int t) {
+  if (b < p.nA) return t;
   b -= p.nA;
-  if (b < p.nB) return p.S + (((int64_t)b * p.stepB) >> 16);
+  if (b < p.nB) return p.S + (((int64_t)(4 * b + (t >> 4)) * p.stepB) >> 16) + (t & 15);
   b -= p.nB;
-  return p.geo.L - 64 * (int64_t)(p.nC - b);
+  return p.geo.L - 64 * (int64_t)(p.nC - b) + t;
 }
 
 // Final selection of the fast path, on the candidate list of each row.

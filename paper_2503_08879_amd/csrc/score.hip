@@ -353,12 +353,11 @@ __global__ __launch_bounds__(kScoreThreads) void sample_logits_kernel(SamplePara
   uint4* buf = lds[wave];
   const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
   const int64_t tok_bytes = p.ks_token * 2;
-  const int64_t tok_base = sample_block_start(p, blk);
 
   uint4 kv[NLOAD];
 #pragma unroll
   for (int i = 0; i < NLOAD; ++i) {
-    int64_t tok = tok_base + i * TPL + tq;
+    int64_t tok = sample_token(p, blk, i * TPL + tq);
     tok = tok < 0 ? 0 : (tok < L ? tok : L - 1);
     kv[i] = ld16(Krow + tok * tok_bytes + cl * 16);
   }

@@ -204,9 +204,9 @@ def test_prefilter_with_one_token_carrying_most_of_the_mass(ref, sampled):
     P, Hq, Hkv, d, L, S, W, k = 1, 4, 1, 128, 40000, 4, 64, 500
     q, K, V = rand_case(21, P, Hq, Hkv, d, L, BF16)
     E = L - S - W
-    n_blocks = max(16, min(128, E // 4096))  # the library samples this many 64-token blocks of candidates
-    start7 = S + ((7 * (((E - 64) << 16) // (n_blocks - 1))) >> 16)
-    t = start7 + 5 + (0 if sampled else 1200)  # inside sample block 7, or between blocks 7 and 8
+    n_runs = 4 * max(16, min(128, E // 4096))  # the library samples this many 16-token runs of candidates
+    start7 = S + ((7 * (((E - 16) << 16) // (n_runs - 1))) >> 16)
+    t = start7 + 5 + (0 if sampled else 300)  # inside sampled run 7, or between runs 7 and 8
     q64 = synth.to_f64(q[0, 0], BF16)
     K[0, 0, t] = synth.round_to_dtype(12.0 * q64 / np.linalg.norm(q64), BF16)  # logit ~ 12
     out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
