@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--config", default="C3", help="C2, C3 (default: the 128K Llama-3.1-8B-shaped target), C4, C5")
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per step (default: the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="before the timed region, run one plain 1 GiB device-to-device copy (a reference of "
+                         "known size for rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--cpu-layers", type=int, default=2)
     ap.add_argument("--cpu-select-seconds", type=float, default=10.0)
     ap.add_argument("--cpu-decode-seconds", type=float, default=5.0)
@@ -152,6 +155,14 @@ def main():
             sk.sagekv_decode_step(ddesc, q_steps[t], kn_steps[t], vn_steps[t], Kc, Vc, t, out, dws)
         if ev:
             ev[2].record()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         one_step()
