@@ -243,6 +243,8 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
   if (p.n_splits > l.max_splits) p.n_splits = l.max_splits;
   const int tps = (len + p.n_splits - 1) / p.n_splits;
   p.tokens_per_split = (tps + 63) / 64 * 64;
+  // a reduced cache that cannot stay in L2 / Infinity Cache between steps is streamed (measured: +8 %)
+  p.stream_loads = 2.0 * l.rows * len * d->head_dim * (d->dtype == SAGEKV_BF16 ? 2 : 4) > 192.0 * 1024 * 1024;
   p.part_ml = (float2*)((char*)ws + l.part_ml);
   p.part_acc = (float*)((char*)ws + l.part_acc);
   p.out = out;

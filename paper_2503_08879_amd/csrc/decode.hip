@@ -75,8 +75,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
       const int tc = valid[i] ? tok : t_begin;
       const char* ks = (tc == slot) ? kn : Kr + (int64_t)tc * ROWB;
       const char* vs = (tc == slot) ? vn : Vr + (int64_t)tc * ROWB;
-      kv[i] = ld16(ks + cl * 16);
-      vv[i] = ld16(vs + cl * 16);
+      kv[i] = p.stream_loads ? ld16_stream(ks + cl * 16) : ld16(ks + cl * 16);
+      vv[i] = p.stream_loads ? ld16_stream(vs + cl * 16) : ld16(vs + cl * 16);
     }
     float x[SB][GB];
 #pragma unroll

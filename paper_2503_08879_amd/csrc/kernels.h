@@ -173,6 +173,7 @@ struct DecodeParams {
   int slot;            // row position the new token takes, -1 = no append
   int len, cap;
   int n_splits, tokens_per_split;
+  int stream_loads;    // reduced cache larger than the on-chip caches: read it with streaming loads
   float* part_acc;     // [rows][n_splits][G][D]
   float2* part_ml;     // [rows][n_splits][G]   (max, sum)
   float* out;          // [P][Hq][D]
