@@ -75,8 +75,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
       const int tc = valid[i] ? tok : t_begin;
       const char* ks = (tc == slot) ? kn : Kr + (int64_t)tc * ROWB;
       const char* vs = (tc == slot) ? vn : Vr + (int64_t)tc * ROWB;
-      kv[i] = p.stream_loads ? ld16_stream(ks + cl * 16) : ld16(ks + cl * 16);
-      vv[i] = p.stream_loads ? ld16_stream(vs + cl * 16) : ld16(vs + cl * 16);
+      kv[i] = ld16(ks + cl * 16);
+      vv[i] = ld16(vs + cl * 16);
     }
     float x[SB][GB];
 #pragma unroll
@@ -167,6 +167,218 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
   }
 }
 
+// bf16 decode with the q.K products on the matrix cores.  Per 32-token block a wave stages K
+// through XOR-swizzled LDS into v_mfma_f32_16x16x32_bf16 (A = queries, zero padded to GPAD heads),
+// so a lane ends with the 4 logits of one token: the softmax weights are computed once per
+// (token, head) instead of once per lane, then handed through LDS to the lanes that hold the V
+// chunks (16 lanes per token, fp32 FMA accumulation).  K and V of block b+1 are both in flight
+// while block b is processed (two 8-load register buffers per wave).  STREAM: the reduced cache
+// does not fit the on-chip caches between steps, read it with streaming loads.
+template <int D, int GPAD, int NW, bool STREAM>
+__global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, int g0, int gb) {
+  constexpr int BT = GPAD > 4 ? 16 : 32;                   // tokens per block (registers: acc is GPAD x 8)
+  constexpr int CH = D / 8, TPL = 64 / CH, NLOAD = BT / TPL, KSTEPS = D / 32;
+  constexpr int TILES = 16 / GPAD;                         // 16-token tiles sharing the accumulator rows
+  constexpr int NT = BT / 16;                              // tiles per block (<= TILES for GPAD <= 8)
+  constexpr int ROWB = D * 2, EPL = 8;
+  constexpr int kThreads = NW * 64;
+  static_assert(NT <= TILES, "one accumulator per block");
+
+  __shared__ uint4 kbuf[NW][BT * CH];
+  __shared__ float pbuf[NW][BT][GPAD];
+  __shared__ float cbuf[NW][GPAD];
+  __shared__ float2 s_ml[NW][GPAD];
+
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int prob = row / p.Hkv, c = row % p.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tq = lane / CH, cl = lane % CH;  // load / PV role: token sub-index, 16-byte chunk
+  const int n = lane & 15, j = lane >> 4;    // MFMA role: column (token), row block
+
+  char* Kr = (char*)p.Kc + (int64_t)row * p.cap * ROWB;
+  char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
+  const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
+  const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
+  const int slot = kn ? p.slot : -1;
+  const int t_begin = split * p.tokens_per_split;
+  const int t_end = min(p.len, t_begin + p.tokens_per_split);
+  if (slot >= t_begin && slot < t_end && tid < CH) {  // Step 4: the new token enters the window
+    st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
+    st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
+  }
+
+  // accumulator rows 4j..4j+3 = (tile slot, heads hbase..hbase+3); slots >= NT stay empty
+  const int hbase = (4 * j) % GPAD, tile = (4 * j) / GPAD;
+  const int t_mine = tile * 16 + n;  // this lane's token within the block (MFMA role)
+  float m_run[4], l_part[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    m_run[r] = -INFINITY;
+    l_part[r] = 0.f;
+  }
+  float acc[GPAD][EPL];
+#pragma unroll
+  for (int g = 0; g < GPAD; ++g)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+
+  uint4* buf = kbuf[wave];
+  const int nblk = (t_end - t_begin + BT - 1) / BT;
+  uint4 kv[NLOAD], vv[NLOAD];
+  auto load_block = [&](int b, uint4* dst, const char* base, const char* fresh) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int tok = t_begin + b * BT + i * TPL + tq;
+      const int tc = tok < t_end ? tok : t_begin;
+      const char* src = (tc == slot) ? fresh : base + (int64_t)tc * ROWB;
+      dst[i] = STREAM ? ld16_stream(src + cl * 16) : ld16(src + cl * 16);
+    }
+  };
+  if (wave < nblk) {  // first blocks in flight before anything else is waited for
+    load_block(wave, kv, Kr, kn);
+    load_block(wave, vv, Vr, vn);
+  }
+  // A operand of tile slot ts, k-step kc, kept in LDS (registers are short here): lane (row m = n,
+  // k-group j) reads q[head m % GPAD][8*(4*kc + j) ..+8] if m / GPAD == ts, zeros otherwise
+  __shared__ uint4 qbuf[NT][KSTEPS][64];
+  for (int it = tid; it < NT * KSTEPS * 64; it += kThreads) {
+    const int l = it & 63, kc = (it >> 6) % KSTEPS, ts = it / (64 * KSTEPS);
+    const int m = l & 15, jj = l >> 4;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (m % GPAD < gb && m / GPAD == ts) {
+      const int h = c * p.G + g0 + m % GPAD;
+      v = ld16((const char*)p.q + (((int64_t)prob * p.Hq + h) * D + (4 * kc + jj) * 8) * 2);
+    }
+    qbuf[ts][kc][l] = v;
+  }
+  __syncthreads();
+  for (int b = wave; b < nblk; b += NW) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // last block's LDS reads are done
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int t = i * TPL + tq;
+      buf[t * CH + (cl ^ (t & (CH - 1)))] = kv[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const bool more = b + NW < nblk;
+    if (more) load_block(b + NW, kv, Kr, kn);
+
+    // logits of the block
+    f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ts = 0; ts < NT; ++ts) {
+      const int t = ts * 16 + n;
+#pragma unroll
+      for (int kc = 0; kc < KSTEPS; ++kc) {
+        const uint4 bb = buf[t * CH + ((4 * kc + j) ^ (n & (CH - 1)))];
+        const uint4 qv = qbuf[ts][kc][lane];
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qv), __builtin_bit_cast(bf16x8_t, bb), d,
+                                                    0, 0, 0);
+      }
+    }
+    const int tok = t_begin + b * BT + t_mine;
+    float x[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) x[r] = (tile < NT && tok < t_end && hbase + r < gb) ? d[r] * p.scale : -INFINITY;
+
+    // online softmax, once per (token, head); lanes with the same heads agree on the maximum
+    float corr[4], pw[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float bm = x[r];
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) bm = fmaxf(bm, __shfl_xor(bm, o));
+#pragma unroll
+      for (int o = 16 * (GPAD / 4); o < 64; o <<= 1) bm = fmaxf(bm, __shfl_xor(bm, o));
+      const float mn = fmaxf(m_run[r], bm);
+      corr[r] = (mn == -INFINITY) ? 1.f : exp_fast(m_run[r] - mn);
+      pw[r] = (x[r] == -INFINITY) ? 0.f : exp_fast(x[r] - mn);
+      l_part[r] = l_part[r] * corr[r] + pw[r];
+      m_run[r] = mn;
+    }
+    if (tile < NT) *reinterpret_cast<float4*>(&pbuf[wave][t_mine][hbase]) = make_float4(pw[0], pw[1], pw[2], pw[3]);
+    if (n == 0 && j < GPAD / 4)
+      *reinterpret_cast<float4*>(&cbuf[wave][hbase]) = make_float4(corr[0], corr[1], corr[2], corr[3]);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    // P.V on the lanes that hold the V chunks
+#pragma unroll
+    for (int g4 = 0; g4 < GPAD / 4; ++g4) {
+      const float4 c4 = *reinterpret_cast<const float4*>(&cbuf[wave][g4 * 4]);
+      const float cr[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g4 * 4 + r][e] *= cr[r];
+    }
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      if (GPAD > 4) __builtin_amdgcn_sched_barrier(0);  // keep the unrolled steps apart: registers
+      const int t_local = i * TPL + tq;
+      float vf[EPL];
+      unpack16<DT_BF16>(vv[i], vf);
+#pragma unroll
+      for (int g4 = 0; g4 < GPAD / 4; ++g4) {
+        const float4 p4 = *reinterpret_cast<const float4*>(&pbuf[wave][t_local][g4 * 4]);
+        const float pp[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g4 * 4 + r][e] = fmaf(pp[r], vf[e], acc[g4 * 4 + r][e]);
+      }
+    }
+    if (more) load_block(b + NW, vv, Vr, vn);
+  }
+
+  // wave totals: sum of weights per head, accumulators over the TPL token groups
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float ls = l_part[r];
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) ls += __shfl_xor(ls, o);
+#pragma unroll
+    for (int o = 16 * (GPAD / 4); o < 64; o <<= 1) ls += __shfl_xor(ls, o);
+    if (n == 0 && j < GPAD / 4) s_ml[wave][hbase + r] = make_float2(m_run[r], ls);
+  }
+  __syncthreads();  // every wave is done with its K buffer: reuse it for the accumulators
+  float* s_acc = reinterpret_cast<float*>(&kbuf[0][0]);  // [NW][GPAD][D]
+  static_assert(GPAD * D * 4 <= BT * CH * 16 + 0 * NW, "accumulators fit the K buffers");
+#pragma unroll
+  for (int g = 0; g < GPAD; ++g)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float a = acc[g][e];
+#pragma unroll
+      for (int o = CH; o < 64; o <<= 1) a += __shfl_xor(a, o);
+      if (tq == 0) s_acc[((wave * GPAD) + g) * D + cl * EPL + e] = a;
+    }
+  __syncthreads();
+
+  const bool single = p.n_splits == 1;
+  float* pa = p.part_acc + (((int64_t)row * p.n_splits + split) * p.G + g0) * D;
+  float2* pml = p.part_ml + ((int64_t)row * p.n_splits + split) * p.G + g0;
+  for (int it = tid; it < gb * D; it += kThreads) {
+    const int g = it / D, jj = it % D;
+    float M = s_ml[0][g].x;
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, s_ml[w][g].x);
+    float a = 0.f, ls = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float2 ml = s_ml[w][g];
+      const float f = (ml.x == -INFINITY) ? 0.f : exp_fast(ml.x - M);
+      a += s_acc[((w * GPAD) + g) * D + jj] * f;
+      ls += ml.y * f;
+    }
+    if (single) {
+      p.out[((int64_t)prob * p.Hq + c * p.G + g0 + g) * D + jj] = a / ls;
+    } else {
+      pa[(int64_t)g * D + jj] = a;
+      if (jj == 0) pml[g] = make_float2(M, ls);
+    }
+  }
+}
+
 // Merges the splits of a row: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
 __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -225,6 +437,25 @@ hipError_t launch_decode_g(const DecodeParams& p, int g0, int gb, dim3 grid, hip
   return hipGetLastError();
 }
 
+template <int D, bool STREAM>
+hipError_t launch_decode_mfma_s(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
+  const bool single = p.n_splits == 1;  // one workgroup per row: 8 waves, else 4
+  if (gb <= 4) {
+    if (single) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+  } else {
+    if (single) hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+  }
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_decode_mfma(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
+  return p.stream_loads ? launch_decode_mfma_s<D, true>(p, g0, gb, grid, s)
+                        : launch_decode_mfma_s<D, false>(p, g0, gb, grid, s);
+}
+
 }  // namespace
 
 hipError_t launch_decode(const DecodeParams& p, hipStream_t s) {
@@ -236,7 +467,7 @@ hipError_t launch_decode(const DecodeParams& p, hipStream_t s) {
     if (g0 > 0) q.k_new = nullptr;  // the first launch already stored the new token
     hipError_t e;
     if (p.dtype == DT_BF16)
-      e = p.D == 128 ? launch_decode_g<DT_BF16, 128>(q, g0, gb, grid, s) : launch_decode_g<DT_BF16, 64>(q, g0, gb, grid, s);
+      e = p.D == 128 ? launch_decode_mfma<128>(q, g0, gb, grid, s) : launch_decode_mfma<64>(q, g0, gb, grid, s);
     else
       e = p.D == 128 ? launch_decode_g<DT_F32, 128>(q, g0, gb, grid, s) : launch_decode_g<DT_F32, 64>(q, g0, gb, grid, s);
     if (e != hipSuccess) return e;
