@@ -47,10 +47,12 @@ typedef enum { SAGEKV_BF16 = 0, SAGEKV_F32 = 1 } sagekv_dtype;
  * "Hq groups of the top-k"; App. A.2).
  *   GROUP_SUM: the heads' softmax probabilities are added and the KV head takes ONE
  *              top-k (the paper prints no operator for this; it is this library's
- *              primary mode).
- *   PER_QUERY: every query head takes its own top-k, the KV head stores G lists
- *              (the paper's literal rule).  Not implemented on the GPU yet:
- *              SAGEKV_ERR_UNSUPPORTED. */
+ *              primary, fastest mode).
+ *   PER_QUERY: the paper's literal rule: every query head takes its own top-k of k tokens by
+ *              its own probabilities, the KV head stores G lists.  A reduced row is then
+ *              [sink | list of head 0 | ... | list of head G-1 | recent], S + G*k + W tokens
+ *              (compact_capacity and kept_idx are sized for that; scores_out is
+ *              [n_problems, Hq, L]); at decode, head g attends sink + its own list + recent. */
 typedef enum { SAGEKV_HEADS_GROUP_SUM = 0, SAGEKV_HEADS_PER_QUERY = 1 } sagekv_head_mode;
 
 /* ---- eviction pass ------------------------------------------------------------------ */
@@ -70,8 +72,8 @@ typedef struct {
   int64_t v_stride_token;
   int32_t n_sink;              /* S >= 0                                                   */
   int32_t n_recent;            /* W >= 1, includes the last token                          */
-  int32_t k;                   /* middle tokens kept per row, 0 <= k <= L - S - W          */
-  int32_t compact_capacity;    /* row pitch (tokens) of Kc / Vc, >= S + k + W              */
+  int32_t k;                   /* middle tokens kept per list, 0 <= k <= L - S - W         */
+  int32_t compact_capacity;    /* row pitch (tokens) of Kc / Vc, >= S + lists*k + W        */
   uint32_t flags;              /* 0, or SAGEKV_SELECT_DENSE                                */
 } sagekv_select_desc;
 
@@ -80,7 +82,8 @@ typedef struct {
  * those; a row whose result cannot be proven equal to the top-k over ALL its candidates is redone
  * by the dense path (every token's score is materialised).  The kept set is the same either way.
  * SAGEKV_SELECT_DENSE forces the dense path for every row; so does a non-null scores_out, an
- * fp32 cache, G > 16, more than 524288 candidates per row, or 5 k + 8192 > L - S - W. */
+ * fp32 cache, PER_QUERY heads, G > 16, more than 524288 candidates per row, or
+ * 5 k + 8192 > L - S - W. */
 enum { SAGEKV_SELECT_DENSE = 1u };
 
 /* Bytes of device scratch sagekv_select needs for this descriptor (0 if it is invalid). */
@@ -112,7 +115,7 @@ sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* desc, const vo
 typedef struct {
   int32_t n_problems, n_q_heads, n_kv_heads, head_dim;
   int32_t dtype;               /* of q, k_new, v_new, Kc, Vc                                */
-  int32_t head_mode;           /* GROUP_SUM only                                            */
+  int32_t head_mode;           /* as in the eviction pass that built the cache              */
   int32_t n_sink, k, n_recent; /* layout of a reduced row: [sink | selected | recent window] */
   int32_t compact_capacity;    /* row pitch of Kc / Vc                                      */
   int32_t grow_recent;         /* 0: the paper's fixed-size FIFO window (Step 4)            */

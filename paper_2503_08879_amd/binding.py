@@ -122,7 +122,8 @@ def select_desc(q_last, K, V, n_sink, n_recent, k, compact_capacity=None, head_m
     P, Hq, d = q_last.shape
     _, Hkv, L, _ = K.shape
     assert K.stride(3) == 1 and V.stride(3) == 1 and q_last.is_contiguous()
-    cap = n_sink + k + n_recent if compact_capacity is None else compact_capacity
+    lists = Hq // Hkv if head_mode == PER_QUERY else 1
+    cap = n_sink + lists * k + n_recent if compact_capacity is None else compact_capacity
     return SelectDesc(P, Hq, Hkv, d, _dtype_of(K), head_mode, L, K.stride(0), K.stride(1), K.stride(2),
                       V.stride(0), V.stride(1), V.stride(2), n_sink, n_recent, k, cap, flags)
 

@@ -33,7 +33,7 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   const int G = d->n_q_heads / d->n_kv_heads;
   const int64_t E = d->L - d->n_sink - d->n_recent;
   f.ok = d->dtype == SAGEKV_BF16 && G <= 16 && d->k > 0 && E <= 524288 && d->L <= 1024 * (int64_t)kScoreChunk &&
-         !(d->flags & SAGEKV_SELECT_DENSE);
+         !(d->flags & SAGEKV_SELECT_DENSE) && (d->head_mode == SAGEKV_HEADS_GROUP_SUM || G == 1);
   if (!f.ok) return f;
   f.cap = (int)(2.5 * d->k) + 4096;
   if ((int64_t)f.cap * 2 > E) {  // k is a large share of the row: the filter would keep most of it
@@ -70,7 +70,7 @@ struct SelectLayout {
       row_fail, fail_list, n_fail;
   FastPlan fast;
   int64_t Lp;
-  int n_chunks, rows, G;
+  int n_chunks, rows, G, n_lists;
 };
 
 bool check_select(const sagekv_select_desc* d, sagekv_status* st) {
@@ -80,13 +80,14 @@ bool check_select(const sagekv_select_desc* d, sagekv_status* st) {
   if (d->L < 1 || d->L > 0x7FFFFFF0ll) return false;
   if (d->n_sink < 0 || d->n_recent < 1 || d->k < 0) return false;
   if ((int64_t)d->n_sink + d->n_recent + d->k > d->L) return false;
-  if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + d->k) return false;
-  if ((int64_t)d->n_problems * d->n_kv_heads > 65535) return false;
+  if (d->head_mode != SAGEKV_HEADS_GROUP_SUM && d->head_mode != SAGEKV_HEADS_PER_QUERY) return false;
+  const int64_t lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? d->n_q_heads / d->n_kv_heads : 1;
+  if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + lists * d->k) return false;
+  if ((int64_t)d->n_problems * d->n_kv_heads * lists > 65535) return false;
   if (d->flags & ~(uint32_t)SAGEKV_SELECT_DENSE) return false;
   *st = SAGEKV_ERR_UNSUPPORTED;
   if (d->dtype != SAGEKV_BF16 && d->dtype != SAGEKV_F32) return false;
   if (d->head_dim != 64 && d->head_dim != 128) return false;
-  if (d->head_mode != SAGEKV_HEADS_GROUP_SUM) return false;
   if (d->n_q_heads / d->n_kv_heads > 64) return false;
   const int epl = d->dtype == SAGEKV_BF16 ? 8 : 4;  // 16-byte alignment of every token row
   const int64_t strides[6] = {d->k_stride_problem, d->k_stride_head, d->k_stride_token,
@@ -104,6 +105,7 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   SelectLayout l;
   l.rows = d->n_problems * d->n_kv_heads;
   l.G = d->n_q_heads / d->n_kv_heads;
+  l.n_lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? l.G : 1;
   l.Lp = (d->L + 3) / 4 * 4;
   l.n_chunks = (int)((d->L + kScoreChunk - 1) / kScoreChunk);
   l.fast = fast_plan(d);
@@ -115,10 +117,10 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   };
   const size_t rows = (size_t)l.rows;
   l.logits = take(rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
-  l.scores = take(own_scores ? rows * l.Lp * sizeof(float) : 0);
+  l.scores = take(own_scores ? rows * l.n_lists * l.Lp * sizeof(float) : 0);
   l.partials = take(rows * l.G * l.n_chunks * sizeof(float2));
   l.stats = take(rows * l.G * sizeof(RowStat));
-  l.ghist = take(rows * kHistBins * sizeof(int));
+  l.ghist = take(rows * l.n_lists * kHistBins * sizeof(int));
   if (l.fast.ok) {
     const FastPlan& f = l.fast;
     const size_t ns = (size_t)64 * (f.nA + f.nB + f.nC);
@@ -141,17 +143,21 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   return l;
 }
 
+int decode_lists(const sagekv_decode_desc* d) {
+  return d->head_mode == SAGEKV_HEADS_PER_QUERY ? d->n_q_heads / d->n_kv_heads : 1;
+}
+
 bool check_decode(const sagekv_decode_desc* d, sagekv_status* st) {
   *st = SAGEKV_ERR_INVALID_ARG;
   if (!d) return false;
   if (d->n_problems < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) return false;
   if (d->n_sink < 0 || d->n_recent < 1 || d->k < 0) return false;
-  if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + d->k) return false;
+  if (d->head_mode != SAGEKV_HEADS_GROUP_SUM && d->head_mode != SAGEKV_HEADS_PER_QUERY) return false;
+  if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + (int64_t)decode_lists(d) * d->k) return false;
   if ((int64_t)d->n_problems * d->n_kv_heads > 65535) return false;
   *st = SAGEKV_ERR_UNSUPPORTED;
   if (d->dtype != SAGEKV_BF16 && d->dtype != SAGEKV_F32) return false;
   if (d->head_dim != 64 && d->head_dim != 128) return false;
-  if (d->head_mode != SAGEKV_HEADS_GROUP_SUM) return false;
   *st = SAGEKV_OK;
   return true;
 }
@@ -244,6 +250,8 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
   const int tps = (len + p.n_splits - 1) / p.n_splits;
   p.tokens_per_split = (tps + 63) / 64 * 64;
   // a reduced cache that cannot stay in L2 / Infinity Cache between steps is streamed (measured: +8 %)
+  p.pq_S = d->n_sink;
+  p.pq_k = decode_lists(d) > 1 ? d->k : 0;
   p.stream_loads = 2.0 * l.rows * len * d->head_dim * (d->dtype == SAGEKV_BF16 ? 2 : 4) > 192.0 * 1024 * 1024;
   p.part_ml = (float2*)((char*)ws + l.part_ml);
   p.part_acc = (float*)((char*)ws + l.part_acc);
@@ -330,6 +338,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   tp.stats = stats;
   tp.G = l.G;
   tp.n_chunks = l.n_chunks;
+  tp.n_lists = l.n_lists;
 
   if (fast) {
     const FastPlan& f = l.fast;
@@ -456,6 +465,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   cp.ghist = ghist;
   cp.S = d->n_sink;
   cp.W = d->n_recent;
+  cp.n_lists = l.n_lists;
   if (!fast) t.begin(SAGEKV_STAGE_COMBINE);
   e = launch_combine(cp, s);
   if (!fast) t.end(SAGEKV_STAGE_COMBINE);
@@ -477,6 +487,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   kp.S = d->n_sink;
   kp.W = d->n_recent;
   kp.k = d->k;
+  kp.n_lists = l.n_lists;
   kp.band = kBand;
   if (!fast) t.begin(SAGEKV_STAGE_TOPK);
   e = launch_topk(kp, s);
@@ -497,7 +508,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   gp.kept_idx = kept_idx;
   gp.Kc = Kc;
   gp.Vc = Vc;
-  gp.n_kept = d->n_sink + d->k + d->n_recent;
+  gp.n_kept = d->n_sink + l.n_lists * d->k + d->n_recent;
   gp.cap = d->compact_capacity;
   t.begin(SAGEKV_STAGE_GATHER);
   e = launch_gather(gp, s);
@@ -528,7 +539,7 @@ sagekv_status sagekv_append(const sagekv_decode_desc* d, const void* k_new, cons
   sagekv_status st;
   if (!check_decode(d, &st)) return st;
   if (!k_new || !v_new || !Kc || !Vc || n_appended < 0) return SAGEKV_ERR_INVALID_ARG;
-  const int base = d->n_sink + d->k;
+  const int base = d->n_sink + decode_lists(d) * d->k;
   const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
   DecodeParams p = {};
@@ -566,7 +577,7 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* d, const void* q, con
   sagekv_status st;
   if (!check_decode(d, &st)) return st;
   if (!q || !k_new || !v_new || !Kc || !Vc || !out || n_appended < 0) return SAGEKV_ERR_INVALID_ARG;
-  const int base = d->n_sink + d->k;
+  const int base = d->n_sink + decode_lists(d) * d->k;
   const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
   const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;

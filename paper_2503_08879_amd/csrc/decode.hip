@@ -84,7 +84,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
         const float v = group_sum<LPT>(dot16<DT>(kv[i], q[g], 0.f)) * p.scale;
-        x[i][g] = valid[i] ? v : -INFINITY;
+        x[i][g] = valid[i] && head_attends(p.pq_S, p.pq_k, p.G, g0 + g, t0 + i * TPL + tq) ? v : -INFINITY;
       }
     float mn[GB];
     bool any = false;
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
     if (any) {  // lanes of one token group agree
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
-        const float corr = exp_fast(m[g] - mn[g]);
+        const float corr = (mn[g] == -INFINITY) ? 1.f : exp_fast(m[g] - mn[g]);  // head with nothing to attend yet
         l[g] *= corr;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
         unpack16<DT>(vv[i], vf);
 #pragma unroll
         for (int g = 0; g < GB; ++g) {
-          const float pw = exp_fast(x[i][g] - mn[g]);
+          const float pw = (x[i][g] == -INFINITY) ? 0.f : exp_fast(x[i][g] - mn[g]);
           l[g] += pw;
 #pragma unroll
           for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw, vf[e], acc[g][e]);
@@ -279,7 +279,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
     const int tok = t_begin + b * BT + t_mine;
     float x[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) x[r] = (tile < NT && tok < t_end && hbase + r < gb) ? d[r] * p.scale : -INFINITY;
+    for (int r = 0; r < 4; ++r)
+      x[r] = (tile < NT && tok < t_end && hbase + r < gb && head_attends(p.pq_S, p.pq_k, p.G, g0 + hbase + r, tok))
+                 ? d[r] * p.scale
+                 : -INFINITY;
 
     // online softmax, once per (token, head); lanes with the same heads agree on the maximum
     float corr[4], pw[4];

@@ -63,8 +63,9 @@ struct StatsParams {
   RowGate gate;
   const float2* partials;
   RowStat* stats;  // [rows][G]
-  int* ghist;      // [rows][kHistBins], zeroed here (nullable)
+  int* ghist;      // [rows * n_lists][kHistBins], zeroed here (nullable)
   int G, n_chunks;
+  int n_lists;     // selection lists per row: 1 (group-sum) or G (per-query)
   // fast path (nullable): bound[row] = upper bound of the exact score of any token the filter dropped
   const float2* samp_stats;
   const float* samp_tau;
@@ -77,10 +78,11 @@ struct CombineParams {
   const float* logits;
   int n_chunks;  // score chunks per row (logit scratch layout)
   const RowStat* stats;
-  float* scores;  // [rows][pitch]
+  float* scores;  // [rows * n_lists][pitch]
   int64_t pitch;
   int* ghist;
   int S, W;
+  int n_lists;    // 1: score = sum over the group's heads; G: one score row per query head
 };
 
 struct TopkParams {
@@ -93,8 +95,9 @@ struct TopkParams {
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;
-  int32_t* kept_idx;  // [rows][S + k + W]
+  int32_t* kept_idx;  // [rows][S + n_lists * k + W]
   int S, W, k;
+  int n_lists;        // 1 or G; list g of a row ranks head g's own probabilities
   float band;  // relative half-width of the fp64 re-evaluation band around the k-th score
 };
 
@@ -174,6 +177,9 @@ struct DecodeParams {
   int len, cap;
   int n_splits, tokens_per_split;
   int stream_loads;    // reduced cache larger than the on-chip caches: read it with streaming loads
+  // per-query head mode: rows are [sink | list of head 0 | ... | list of head G-1 | recent]; head g
+  // attends the sink, its own list and the recent window.  pq_k = 0: every head attends everything.
+  int pq_S, pq_k;
   float* part_acc;     // [rows][n_splits][G][D]
   float2* part_ml;     // [rows][n_splits][G]   (max, sum)
   float* out;          // [P][Hq][D]
@@ -193,6 +199,12 @@ hipError_t launch_gather(const GatherParams& p, hipStream_t s);
 hipError_t launch_decode(const DecodeParams& p, hipStream_t s);
 hipError_t launch_append(const DecodeParams& p, hipStream_t s);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t s);
+
+// Does query head g (index inside its group of G) attend position tok of a reduced row?
+__host__ __device__ inline bool head_attends(int pq_S, int pq_k, int G, int g, int tok) {
+  if (pq_k <= 0 || tok < pq_S || tok >= pq_S + G * pq_k) return true;
+  return (tok - pq_S) / pq_k == g;
+}
 
 int max_group_per_launch();  // heads of a group one score / decode launch can hold in registers
 

@@ -83,16 +83,16 @@ __device__ inline double elem_f64<DT_F32>(const void* base, int64_t i) {
   return (double)((const float*)base)[i];
 }
 
-// Score of token `tok` of the row in fp64, rounded once to fp32.
+// Score of token `tok` of the row in fp64 (heads g_lo .. g_hi-1 of the group), rounded once to fp32.
 template <int DT>
 __device__ inline float refined_score(const RowGeom& geo, const void* q_last, const void* K, int64_t ks_problem,
                                    int64_t ks_head, int64_t ks_token, const RowStat* stats, int prob, int c, int row,
-                                   int64_t tok) {
+                                   int64_t tok, int g_lo, int g_hi) {
   const int D = geo.D, G = geo.G;
   const int64_t k_off = (int64_t)prob * ks_problem + (int64_t)c * ks_head + tok * ks_token;
   const double inv = 1.0 / sqrt((double)D);
   double tot = 0.0;
-  for (int g = 0; g < G; ++g) {
+  for (int g = g_lo; g < g_hi; ++g) {
     const int64_t q_off = ((int64_t)prob * geo.Hq + c * G + g) * D;
     double acc = 0.0;
     for (int j = 0; j < D; ++j) acc += elem_f64<DT>(q_last, q_off + j) * elem_f64<DT>(K, k_off + j);

@@ -408,7 +408,7 @@ __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
     row = p.gate.row_map[blockIdx.x];
   }
   if (p.ghist)
-    for (int b = lane; b < kHistBins; b += 64) p.ghist[(int64_t)row * kHistBins + b] = 0;
+    for (int b = lane; b < kHistBins * p.n_lists; b += 64) p.ghist[(int64_t)row * p.n_lists * kHistBins + b] = 0;
   double rho = 0.0;  // max over heads of (exact softmax weight) / (sampled softmax weight)
   for (int g = 0; g < p.G; ++g) {
     const float2* pr = p.partials + ((int64_t)row * p.G + g) * p.n_chunks;
@@ -462,7 +462,10 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     sInv[tid] = st.invZ;
   }
   __syncthreads();
-  float* out = p.scores + (int64_t)row * p.pitch;
+  // group-sum: one score row per KV head; per-query: blockIdx.z picks the head, one row each
+  const int g_lo = p.n_lists > 1 ? blockIdx.z : 0, g_hi = p.n_lists > 1 ? g_lo + 1 : G;
+  const int64_t list = (int64_t)row * p.n_lists + (p.n_lists > 1 ? g_lo : 0);
+  float* out = p.scores + list * p.pitch;
   const int64_t cand_lo = p.S, cand_hi = L - p.W;
   const bool vec_out = (p.pitch & 3) == 0;
   const int64_t base = (int64_t)blockIdx.x * kCombineChunk;
@@ -471,7 +474,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     const int64_t tok = base + (int64_t)it * kCombineThreads * 4 + tid * 4;
     if (tok >= L) break;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int g = 0; g < G; ++g) {
+    for (int g = g_lo; g < g_hi; ++g) {
       const float4 x = *reinterpret_cast<const float4*>(p.logits + logit_index(p.geo, p.n_chunks, row, g, tok));
       const float M = sM[g], inv = sInv[g];
       acc[0] += exp_accurate(x.x - M) * inv;
@@ -493,7 +496,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     }
   }
   __syncthreads();
-  int* gh = p.ghist + (int64_t)row * kHistBins;
+  int* gh = p.ghist + list * kHistBins;
   for (int b = tid; b < kHistBins; b += kCombineThreads) {
     int v = hist[b];
     if (v) atomicAdd(&gh[b], v);
@@ -583,7 +586,7 @@ hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s) {
 hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
   const int rows = p.geo.n_problems * p.geo.Hkv;
   const unsigned nx = (unsigned)((p.geo.L + kCombineChunk - 1) / kCombineChunk);
-  hipLaunchKernelGGL(combine_kernel, dim3(nx, (unsigned)rows), dim3(kCombineThreads), 0, s, p);
+  hipLaunchKernelGGL(combine_kernel, dim3(nx, (unsigned)rows, (unsigned)p.n_lists), dim3(kCombineThreads), 0, s, p);
   return hipGetLastError();
 }
 

@@ -26,24 +26,29 @@ template <int DT>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   __shared__ TopkShared sh;
   const int tid = threadIdx.x;
-  int row = blockIdx.x;
-  if (p.gate.row_map) {
+  int list = blockIdx.x;  // selection list: one per row (group-sum) or one per (row, query head)
+  if (p.gate.row_map) {   // gated launches are group-sum only: list = row
     if ((int)blockIdx.x >= *p.gate.n_active) return;
-    row = p.gate.row_map[blockIdx.x];
+    list = p.gate.row_map[blockIdx.x];
   }
+  const int row = list / p.n_lists, gl = list % p.n_lists;
+  const int g_lo = p.n_lists > 1 ? gl : 0, g_hi = p.n_lists > 1 ? gl + 1 : p.geo.G;
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int S = p.S, W = p.W, k = p.k;
   const int64_t L = p.geo.L, E = L - S - W;
-  const int n_kept = S + k + W;
-  int32_t* kept = p.kept_idx + (int64_t)row * n_kept;
-  float* cand = p.scores + (int64_t)row * p.pitch + S;
+  const int n_kept = S + p.n_lists * k + W;
+  int32_t* kept_row = p.kept_idx + (int64_t)row * n_kept;
+  int32_t* kept = kept_row + gl * k;  // this list's k slots start at kept[S]
+  float* cand = p.scores + (int64_t)list * p.pitch + S;
 
-  for (int t = tid; t < S; t += kTopkThreads) kept[t] = t;
-  for (int t = tid; t < W; t += kTopkThreads) kept[S + k + t] = (int32_t)(L - W + t);
+  if (gl == 0) {
+    for (int t = tid; t < S; t += kTopkThreads) kept_row[t] = t;
+    for (int t = tid; t < W; t += kTopkThreads) kept_row[S + p.n_lists * k + t] = (int32_t)(L - W + t);
+  }
   if (k == 0) return;
 
   // 1. coarse threshold from the fp32 scores
-  for (int b = tid; b < kHistBins; b += kTopkThreads) sh.hist[b] = p.ghist[(int64_t)row * kHistBins + b];
+  for (int b = tid; b < kHistBins; b += kTopkThreads) sh.hist[b] = p.ghist[(int64_t)list * kHistBins + b];
   __syncthreads();
   uint32_t tau;
   int quota;
@@ -54,7 +59,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
   for (int64_t i = tid; i < E; i += kTopkThreads) {
     const float v = cand[i];
-    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, S + i);
+    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, S + i,
+                                 g_lo, g_hi);
   }
   __syncthreads();
 
@@ -129,11 +135,11 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
 }  // namespace
 
 hipError_t launch_topk(const TopkParams& p, hipStream_t s) {
-  const int rows = p.geo.n_problems * p.geo.Hkv;
+  const int lists = p.geo.n_problems * p.geo.Hkv * p.n_lists;
   if (p.geo.dtype == DT_BF16)
-    hipLaunchKernelGGL(topk_kernel<DT_BF16>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
+    hipLaunchKernelGGL(topk_kernel<DT_BF16>, dim3((unsigned)lists), dim3(kTopkThreads), 0, s, p);
   else
-    hipLaunchKernelGGL(topk_kernel<DT_F32>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
+    hipLaunchKernelGGL(topk_kernel<DT_F32>, dim3((unsigned)lists), dim3(kTopkThreads), 0, s, p);
   return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ def have_gpu() -> bool:
     return torch.cuda.is_available()
 
 
-def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, V_dev=None, flags=0):
+def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, V_dev=None, flags=0, head_mode=0):
     """q [P,Hq,d], K/V [P,Hkv,L,d] host arrays (or device tensors via K_dev/V_dev).
     Returns dict of host arrays: Kc, Vc, kept, scores."""
     import torch
@@ -29,14 +29,15 @@ def gpu_select(dtype, q, K, V, S, W, k, cap=None, want_scores=True, K_dev=None, 
     Vd = V_dev if V_dev is not None else synth.host_to_torch(V, dtype)
     P, Hq, d = qd.shape
     Hkv, L = Kd.shape[1], Kd.shape[2]
-    n_kept = S + k + W
+    lists = Hq // Hkv if head_mode == 1 else 1
+    n_kept = S + lists * k + W
     cap = n_kept if cap is None else cap
-    desc = sk.select_desc(qd, Kd, Vd, S, W, k, cap, flags=flags)
+    desc = sk.select_desc(qd, Kd, Vd, S, W, k, cap, flags=flags, head_mode=head_mode)
     ws = torch.empty(max(sk.sagekv_select_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
     Kc = torch.zeros((P, Hkv, cap, d), dtype=Kd.dtype, device="cuda")
     Vc = torch.zeros((P, Hkv, cap, d), dtype=Kd.dtype, device="cuda")
     kept = torch.full((P, Hkv, n_kept), -1, dtype=torch.int32, device="cuda")
-    scores = torch.empty((P, Hkv, L), dtype=torch.float32, device="cuda") if want_scores else None
+    scores = torch.empty((P, Hkv * lists, L), dtype=torch.float32, device="cuda") if want_scores else None
     sk.sagekv_select(desc, qd, Kd, Vd, Kc, Vc, kept, scores, ws)
     torch.cuda.synchronize()
     return {
@@ -89,12 +90,12 @@ def check_gather(out, K, V, S, k, W):
             np.testing.assert_array_equal(out["Vc"][p, c, :n], V[p, c][kept[p, c]])
 
 
-def gpu_decode_setup(dtype, P, Hq, Hkv, d, S, k, W, cap, grow=False):
+def gpu_decode_setup(dtype, P, Hq, Hkv, d, S, k, W, cap, grow=False, head_mode=0):
     import torch
 
     import paper_2503_08879_amd as sk
 
-    desc = sk.decode_desc(P, Hq, Hkv, d, dtype, S, k, W, cap, grow)
+    desc = sk.decode_desc(P, Hq, Hkv, d, dtype, S, k, W, cap, grow, head_mode=head_mode)
     ws = torch.empty(max(sk.sagekv_decode_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
     out = torch.empty((P, Hq, d), dtype=torch.float32, device="cuda")
     return desc, ws, out

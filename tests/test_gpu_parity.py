@@ -243,7 +243,7 @@ def test_invalid_arguments_are_rejected_before_launch():
     good = sk.select_desc(q, K, K, 4, 32, 64, 100)
     call(good)
     for field, value, code in [("k", 600, 1), ("n_recent", 0, 1), ("compact_capacity", 50, 1), ("n_q_heads", 3, 1),
-                               ("head_dim", 96, 2), ("dtype", 5, 2), ("head_mode", 1, 2), ("k_stride_token", 100, 2)]:
+                               ("head_dim", 96, 2), ("dtype", 5, 2), ("head_mode", 7, 1), ("k_stride_token", 100, 2)]:
         bad = sk.select_desc(q, K, K, 4, 32, 64, 100)
         setattr(bad, field, value)
         kept.fill_(-7)
@@ -392,3 +392,65 @@ def test_C1_end_to_end(ref):
         sk.sagekv_decode_step(desc, qd, knd, vnd, out["Kc_dev"], out["Vc_dev"], t, o, ws)
         torch.cuda.synchronize()
         assert np.abs(o.cpu().numpy() - want).max() <= gu.DECODE_ATOL[cfg.dtype]
+
+
+# ----------------------------------------------------------------------------- per-query head mode (paper-literal)
+def per_query_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps, seed):
+    """Select with one top-k per query head, then decode steps where head g attends sink + its own
+    list + recent (Sec. 2 Step 2, App. A.2)."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    G = Hq // Hkv
+    q, K, V = rand_case(seed, P, Hq, Hkv, d, L, dtype)
+    out = gu.gpu_select(dtype, q, K, V, S, W, k, head_mode=1)
+    Kc, Vc, kept, s = ref.select(dtype, 1, q, K, V, S, W, k, want_scores=True)  # s [P,Hkv,G,L]
+    gu.check_scores(out["scores"].reshape(P, Hkv, G, L), s)
+    n_kept = S + G * k + W
+    assert out["kept"].shape[-1] == n_kept
+    n_ex = 0
+    for g in range(G):  # every list against the oracle's, with the near-tie exemption
+        sub_gpu = np.concatenate([out["kept"][..., :S], out["kept"][..., S + g * k:S + (g + 1) * k],
+                                  out["kept"][..., S + G * k:]], axis=-1)
+        sub_ref = np.concatenate([kept[..., :S], kept[..., S + g * k:S + (g + 1) * k], kept[..., S + G * k:]], axis=-1)
+        n_ex += gu.check_kept(sub_gpu, sub_ref, s[:, :, g], S, W, k)
+    gu.check_gather(out, K, V, S, G * k, W)
+    if n_ex:
+        return
+    np.testing.assert_array_equal(out["Kc"], Kc)
+    np.testing.assert_array_equal(out["Vc"], Vc)
+    desc, ws, o = gu.gpu_decode_setup(dtype, P, Hq, Hkv, d, S, k, W, n_kept, head_mode=1)
+    key = synth.stream_key(seed, 91)
+    for t in range(steps):
+        qs = synth.fill_host(key, t * 1_000_000, P * Hq * d, dtype).reshape(P, Hq, d)
+        kn = synth.fill_host(key, (1 << 30) + t * 1_000_000, P * Hkv * d, dtype).reshape(P, Hkv, d)
+        vn = synth.fill_host(key, (2 << 30) + t * 1_000_000, P * Hkv * d, dtype).reshape(P, Hkv, d)
+        ref.append(dtype, Kc, Vc, kn, vn, S + G * k, W)
+        want = ref.decode_attn(dtype, 1, qs, Kc, Vc, 0, S, k, W)
+        sk.sagekv_decode_step(desc, *(synth.host_to_torch(x, dtype) for x in (qs, kn, vn)), out["Kc_dev"],
+                              out["Vc_dev"], t, o, ws)
+        torch.cuda.synchronize()
+        err = np.abs(o.cpu().numpy() - want).max()
+        assert err <= gu.DECODE_ATOL[dtype], f"step {t}: {err:.3e}"
+
+
+@pytest.mark.parametrize(
+    "dtype,P,Hq,Hkv,d,L,S,W,k,steps",
+    [
+        (F32, 1, 4, 2, 64, 4096, 4, 64, 94, 8),        # config C1 with k = 94 per query head
+        (BF16, 2, 8, 2, 128, 6000, 16, 40, 150, 45),   # G=4, window wraps
+        (BF16, 1, 7, 1, 128, 5000, 3, 17, 99, 4),      # G=7
+        (BF16, 3, 4, 4, 64, 3000, 0, 1, 50, 3),        # G=1: same as group-sum
+        (F32, 1, 6, 2, 128, 2000, 5, 33, 0, 3),        # k = 0
+    ],
+)
+def test_per_query_mode(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps):
+    per_query_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps, seed=300 + Hq + d)
+
+
+def test_per_query_paper_budget(ref):
+    """The appendix's split for Llama (B = 8192, G = 4): sink 2048, 1024 per query head, recent 2048,
+    on a 32K-token bf16 cache of two Llama-shaped layers."""
+    sink, k, recent = ref.paper_budget(8192, 4)
+    per_query_case(ref, BF16, 2, 32, 8, 128, 32768, sink, recent, k, 2, seed=77)
