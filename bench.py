@@ -27,12 +27,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
-def algorithmic_bytes(cfg):
+def algorithmic_bytes(cfg, budget=None):
     """(select bytes per pass, decode bytes per decode step, score-kernel bytes per launch)."""
     e, d = cfg.elem_bytes, cfg.head_dim
-    per_row = cfg.L * d * e + 4 * cfg.budget * d * e + 4 * cfg.budget
+    budget = cfg.budget if budget is None else budget
+    per_row = cfg.L * d * e + 4 * budget * d * e + 4 * budget
     select = cfg.rows * per_row
-    decode = 2 * cfg.rows * cfg.budget * d * e
+    decode = 2 * cfg.rows * budget * d * e
     score = cfg.rows * cfg.L * d * e
     return select, decode, score
 
@@ -99,6 +100,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="C3", help="C2, C3 (default: the 128K Llama-3.1-8B-shaped target), C4, C5")
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per step (default: the config's)")
+    ap.add_argument("--per-query-budget", type=int, default=0, metavar="B",
+                    help="paper-literal head mode: one top-k per query head with the appendix's split of a token "
+                         "budget B (sink B/4, k = pow2floor(B/2G) per head, recent = rest) instead of the config's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, run one plain 1 GiB device-to-device copy (a reference of "
@@ -119,10 +123,20 @@ def main():
     import synth
 
     cfg = synth.CONFIGS[args.config]
+    head_mode, lists = sk.GROUP_SUM, 1
+    if args.per_query_budget:
+        B, G = args.per_query_budget, cfg.G
+        kk = 1
+        while 2 * kk <= B // (2 * G):
+            kk *= 2
+        cfg = cfg.with_(n_sink=B // 4, k=kk, n_recent=B - B // 4 - G * kk)
+        head_mode, lists = sk.PER_QUERY, G
+        args.no_cpu_baseline = True
     n_dec = cfg.decode_steps if args.decode_steps is None else args.decode_steps
     torch.cuda.set_device(0)
     dev = "cuda"
-    S, W, k, Bt = cfg.n_sink, cfg.n_recent, cfg.k, cfg.budget
+    S, W, k = cfg.n_sink, cfg.n_recent, cfg.k
+    Bt = S + lists * k + W
 
     # ---- inputs, resident in HBM
     q_last, K, V, _ = synth.kv_device(cfg, dev)
@@ -136,12 +150,12 @@ def main():
     synth.fill_device(vn_steps, synth.stream_key(cfg.seed, synth.T_VNEW))
 
     # ---- outputs and workspaces (allocated once, outside the timed region)
-    sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt)
+    sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt, head_mode=head_mode)
     sws = torch.empty(sk.sagekv_select_workspace_bytes(sdesc), dtype=torch.uint8, device=dev)
     Kc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
     Vc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
     kept = torch.zeros((P, Hkv, Bt), dtype=torch.int32, device=dev)
-    ddesc = sk.decode_desc(P, Hq, Hkv, d, cfg.dtype, S, k, W, Bt)
+    ddesc = sk.decode_desc(P, Hq, Hkv, d, cfg.dtype, S, k, W, Bt, head_mode=head_mode)
     dws = torch.empty(sk.sagekv_decode_workspace_bytes(ddesc), dtype=torch.uint8, device=dev)
     out = torch.empty((P, Hq, d), dtype=torch.float32, device=dev)
 
@@ -185,7 +199,7 @@ def main():
     dec_kernel_ms = float(np.mean([sk.sagekv_stage_timing_read(1, i)[0] for i in range(n_dec_timed)])) if n_dec else None
     sk.sagekv_stage_timing_enable(0)
 
-    sel_b, dec_b, score_b = algorithmic_bytes(cfg)
+    sel_b, dec_b, score_b = algorithmic_bytes(cfg, Bt)
     ms_per_step = elapsed / args.steps * 1e3
     total_b = sel_b + n_dec * dec_b
     value = total_b / (ms_per_step * 1e-3) / 1e9
@@ -211,7 +225,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{cfg.name}: {cfg.n_layers} layers x batch {cfg.batch}, {Hq}q/{Hkv}kv heads, head_dim {d}, "
-                        f"L={cfg.L}, budget {Bt} = {S} sink + {k} top-k + {W} recent, {n_dec} decode steps per step",
+                        f"L={cfg.L}, budget {Bt} = {S} sink + {lists}x{k} top-k + {W} recent, {n_dec} decode steps per step"
+                        + (", one top-k per query head" if lists > 1 else ""),
             "rows": cfg.rows,
             "step": "1 eviction pass over the whole cache + the decode steps",
         },

@@ -33,9 +33,10 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   const int G = d->n_q_heads / d->n_kv_heads;
   const int64_t E = d->L - d->n_sink - d->n_recent;
   f.ok = d->dtype == SAGEKV_BF16 && G <= 16 && d->k > 0 && E <= 524288 && d->L <= 1024 * (int64_t)kScoreChunk &&
-         !(d->flags & SAGEKV_SELECT_DENSE) && (d->head_mode == SAGEKV_HEADS_GROUP_SUM || G == 1);
+         !(d->flags & SAGEKV_SELECT_DENSE);
   if (!f.ok) return f;
-  f.cap = (int)(2.5 * d->k) + 4096;
+  const int lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? G : 1;
+  f.cap = (int)(2.5 * d->k) * lists + 4096;  // per-query lists share one candidate list per row
   if ((int64_t)f.cap * 2 > E) {  // k is a large share of the row: the filter would keep most of it
     f.ok = false;
     return f;
@@ -127,14 +128,14 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
     l.samp_logit = take(rows * ns * f.Gs * sizeof(float));
     l.samp_score = take(0);
     l.samp_stats = take(rows * l.G * sizeof(float2));
-    l.samp_tau = take(rows * sizeof(float));
+    l.samp_tau = take(rows * l.n_lists * sizeof(float));
     const size_t slots = rows * l.n_chunks * kScoreChunk;  // every token has a slot: chunks cannot overflow
     l.cand_count = take(rows * l.n_chunks * sizeof(int));
     l.cand_idx = take(slots * sizeof(int32_t));
     l.cand_logit = take(slots * f.Gs * sizeof(float));
-    l.cand_score = take(rows * f.cap * sizeof(float));
-    l.cand_pos = take(rows * f.cap * sizeof(int32_t));
-    l.bound = take(rows * sizeof(float));
+    l.cand_score = take(rows * l.n_lists * f.cap * sizeof(float));
+    l.cand_pos = take(rows * l.n_lists * f.cap * sizeof(int32_t));
+    l.bound = take(rows * l.n_lists * sizeof(float));
     l.row_fail = take(rows * sizeof(int));
     l.fail_list = take(rows * sizeof(int));
     l.n_fail = take(sizeof(int));
@@ -372,6 +373,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
     mp.wB = f.wB;
     mp.wC = f.wC;
     mp.rank = f.rank;
+    mp.n_lists = l.n_lists;
     mp.Gs = f.Gs;
     mp.samp_logit = (float*)(ws + l.samp_logit);
     mp.samp_stats = samp_stats;
@@ -390,6 +392,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
     fp.filt.cand_idx = cand_idx;
     fp.filt.cand_logit = cand_logit;
     fp.filt.Gs = f.Gs;
+    fp.filt.n_lists = l.n_lists;
     fp.filt.S = d->n_sink;
     fp.filt.W = d->n_recent;
     t.begin(SAGEKV_STAGE_SCORE);
@@ -419,6 +422,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
     cp.cand_pos = (int32_t*)(ws + l.cand_pos);
     cp.cap = f.cap;
     cp.Gs = f.Gs;
+    cp.n_lists = l.n_lists;
     cp.q_last = q_last;
     cp.K = K;
     cp.ks_problem = d->k_stride_problem;

@@ -37,7 +37,9 @@ struct RowGate {
 // writing every token's logits.
 struct FilterParams {
   const float2* samp_stats;  // [rows][G]  (M^, 1/Z^) from the sample
-  const float* samp_tau;     // [rows]     threshold on the approximate score
+  const float* samp_tau;     // [rows * n_lists] threshold on the approximate score (per head if n_lists = G)
+  int n_lists;               // 1: the group's summed score is compared; G: a token passes if ANY head's
+                             //    own probability reaches that head's threshold
   int* cand_count;           // [rows][n_chunks]               candidates each score workgroup kept
   int32_t* cand_idx;         // [rows][n_chunks][kScoreChunk]  a workgroup owns its chunk's slots: no
   float* cand_logit;         // [rows][n_chunks][kScoreChunk][Gs]   global atomics, no overflow
@@ -66,10 +68,10 @@ struct StatsParams {
   int* ghist;      // [rows * n_lists][kHistBins], zeroed here (nullable)
   int G, n_chunks;
   int n_lists;     // selection lists per row: 1 (group-sum) or G (per-query)
-  // fast path (nullable): bound[row] = upper bound of the exact score of any token the filter dropped
+  // fast path (nullable): bound[list] = upper bound of the exact score of any token the filter dropped
   const float2* samp_stats;
   const float* samp_tau;
-  float* bound;
+  float* bound;  // [rows * n_lists]
 };
 
 struct CombineParams {
@@ -116,10 +118,11 @@ struct SampleParams {
   int validA, validC;   // sink tokens in block A; recent tokens covered by the C blocks
   float wA, wB, wC;     // tokens of the row one sampled token stands for
   int rank;             // rank (1-based) of the threshold among the 64 * nB sampled candidates
+  int n_lists;          // 1: one threshold on the summed score; G: one per query head
   int Gs;               // heads per token in samp_logit (G rounded up to a multiple of 4)
   float* samp_logit;    // [rows][64 * (nA + nB + nC)][Gs] scratch
   float2* samp_stats;   // out [rows][G]
-  float* samp_tau;      // out [rows]
+  float* samp_tau;      // out [rows * n_lists]
   int* row_fail;        // out [rows] = 0
   float scale;
 };
@@ -143,9 +146,10 @@ struct TopkCandParams {
   const int32_t* cand_idx;
   const float* cand_logit;
   int n_chunks;
-  float* cand_score;         // [rows][cap] scratch: exact scores of the row's candidates, dense
-  int32_t* cand_pos;         // [rows][cap] scratch: their token indices
+  float* cand_score;         // [rows * n_lists][cap] scratch: exact scores of the candidates, dense
+  int32_t* cand_pos;         // [rows * n_lists][cap] scratch: their token indices
   int cap, Gs;
+  int n_lists;               // 1 or G: list g of a row ranks head g's own probability
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;

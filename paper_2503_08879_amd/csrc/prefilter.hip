@@ -92,21 +92,26 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
   }
   __syncthreads();
 
-  for (int s = tid; s < nB; s += kTopkThreads) {
-    const float* lg = slog + (int64_t)(64 * p.nA + s) * Gs;
-    float a = 0.f;
-    for (int g = 0; g < G; ++g) a += exp_fast(lg[g] - sM[g]) * sInv[g];
-    ss[s] = a;
+  // group-sum: one threshold on the summed approximate score; per-query: one per head on its own
+  for (int li = 0; li < p.n_lists; ++li) {
+    const int g_lo = p.n_lists > 1 ? li : 0, g_hi = p.n_lists > 1 ? li + 1 : G;
+    __syncthreads();
+    for (int s = tid; s < nB; s += kTopkThreads) {
+      const float* lg = slog + (int64_t)(64 * p.nA + s) * Gs;
+      float a = 0.f;
+      for (int g = g_lo; g < g_hi; ++g) a += exp_fast(lg[g] - sM[g]) * sInv[g];
+      ss[s] = a;
+    }
+    __syncthreads();
+    float tau_f = 0.f;  // rank beyond the sample: everything passes (the row is then redone densely)
+    if (p.rank >= 1 && p.rank <= nB) {
+      uint32_t tau;
+      int quota;
+      radix_select(sh, ss, nB, p.rank, false, &tau, &quota);
+      tau_f = __uint_as_float(tau);
+    }
+    if (tid == 0) p.samp_tau[(int64_t)row * p.n_lists + li] = tau_f;
   }
-  __syncthreads();
-  float tau_f = 0.f;  // rank beyond the sample: everything passes (the row is then redone densely)
-  if (p.rank >= 1 && p.rank <= nB) {
-    uint32_t tau;
-    int quota;
-    radix_select(sh, ss, nB, p.rank, false, &tau, &quota);
-    tau_f = __uint_as_float(tau);
-  }
-  if (tid == 0) p.samp_tau[row] = tau_f;
 }
 
 template <int DT>
@@ -118,15 +123,20 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   __shared__ int n_band, n_above;
   extern __shared__ uint32_t bitmap[];  // one bit per eviction candidate of the row
 
-  const int row = blockIdx.x, tid = threadIdx.x;
+  const int list = blockIdx.x, tid = threadIdx.x;  // one list per row, or one per (row, query head)
+  const int row = list / p.n_lists, gl = list % p.n_lists;
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int S = p.S, W = p.W, k = p.k, G = p.geo.G;
+  const int g_lo = p.n_lists > 1 ? gl : 0, g_hi = p.n_lists > 1 ? gl + 1 : G;
   const int64_t L = p.geo.L, E = L - S - W;
-  const int n_kept = S + k + W;
-  int32_t* kept = p.kept_idx + (int64_t)row * n_kept;
+  const int n_kept = S + p.n_lists * k + W;
+  int32_t* kept_row = p.kept_idx + (int64_t)row * n_kept;
+  int32_t* kept = kept_row + gl * k;  // this list's k slots start at kept[S]
 
-  for (int t = tid; t < S; t += kTopkThreads) kept[t] = t;
-  for (int t = tid; t < W; t += kTopkThreads) kept[S + k + t] = (int32_t)(L - W + t);
+  if (gl == 0) {
+    for (int t = tid; t < S; t += kTopkThreads) kept_row[t] = t;
+    for (int t = tid; t < W; t += kTopkThreads) kept_row[S + p.n_lists * k + t] = (int32_t)(L - W + t);
+  }
   if (k == 0) return;
 
   // candidates per score chunk -> offsets of a dense list
@@ -153,8 +163,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   }
 
   // exact fp32 scores of the candidates (same arithmetic and order as the dense combine stage)
-  float* cs = p.cand_score + (int64_t)row * p.cap;
-  int32_t* ci = p.cand_pos + (int64_t)row * p.cap;
+  float* cs = p.cand_score + (int64_t)list * p.cap;
+  int32_t* ci = p.cand_pos + (int64_t)list * p.cap;
   for (int d0 = 0; d0 < n_c; d0 += 4 * kTopkThreads) {
     int64_t slot[4];
 #pragma unroll
@@ -188,7 +198,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
             const float x[4] = {lg[u][g4].x, lg[u][g4].y, lg[u][g4].z, lg[u][g4].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (g4 * 4 + e < G) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
+              if (g4 * 4 + e >= g_lo && g4 * 4 + e < g_hi) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
           }
         cs[dj] = a;
         ci[dj] = ti[u];
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
   // every token outside the list scores below bound[row]: the row is certified only if no such
   // token can reach the band
-  if (!(lo * (1.0f - p.band) > p.bound[row])) {
+  if (!(lo * (1.0f - p.band) > p.bound[list])) {
     if (tid == 0) p.row_fail[row] = 1;
     return;
   }
@@ -236,7 +246,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   for (int t = tid >> 6; t < nb; t += kTopkWaves) {
     const int tok = ci[band_j[t]];
     const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c,
-                                           row, tok);
+                                           row, tok, g_lo, g_hi);
     if ((tid & 63) == 0) {
       band_v[t] = v;
       band_tok[t] = tok;
@@ -308,7 +318,7 @@ hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(topk_cand_kernel<DT_BF16>, dim3((unsigned)rows), dim3(kTopkThreads), lds, s, p);
+  hipLaunchKernelGGL(topk_cand_kernel<DT_BF16>, dim3((unsigned)(rows * p.n_lists)), dim3(kTopkThreads), lds, s, p);
   return hipGetLastError();
 }
 

@@ -107,12 +107,12 @@ __device__ inline float refined_score(const RowGeom& geo, const void* q_last, co
 template <int DT>
 __device__ inline float refined_score_wave(const RowGeom& geo, const void* q_last, const void* K, int64_t ks_problem,
                                         int64_t ks_head, int64_t ks_token, const RowStat* stats, int prob, int c,
-                                        int row, int64_t tok) {
+                                        int row, int64_t tok, int g_lo, int g_hi) {
   const int D = geo.D, G = geo.G, lane = threadIdx.x & 63;
   const int64_t k_off = (int64_t)prob * ks_problem + (int64_t)c * ks_head + tok * ks_token;
   const double inv = 1.0 / sqrt((double)D);
   double tot = 0.0;
-  for (int g = 0; g < G; ++g) {
+  for (int g = g_lo; g < g_hi; ++g) {
     const int64_t q_off = ((int64_t)prob * geo.Hq + c * G + g) * D;
     double acc = 0.0;
     for (int j = lane; j < D; j += 64) acc += elem_f64<DT>(q_last, q_off + j) * elem_f64<DT>(K, k_off + j);

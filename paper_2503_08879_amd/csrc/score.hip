@@ -189,6 +189,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
 
   // filter state: approximate softmax weights of this lane's 4 heads, the row's threshold
   float fM[4] = {0.f, 0.f, 0.f, 0.f}, fInv[4] = {0.f, 0.f, 0.f, 0.f}, ftau = 0.f;
+  float ftau_h[4] = {INFINITY, INFINITY, INFINITY, INFINITY};  // per-query lists: a threshold per head
+  const bool per_head = FILTER && p.filt.n_lists > 1;
   if (FILTER) {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -196,8 +198,9 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
         const float2 st = p.filt.samp_stats[(int64_t)row * p.geo.G + hbase + r];
         fM[r] = st.x;
         fInv[r] = st.y;
+        if (per_head) ftau_h[r] = p.filt.samp_tau[(int64_t)row * p.geo.G + hbase + r];
       }
-    ftau = p.filt.samp_tau[row];
+    if (!per_head) ftau = p.filt.samp_tau[row];
     if (threadIdx.x == 0) n_kept_wg = 0;
     __syncthreads();
   }
@@ -258,6 +261,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
       for (int a = 0; a < NACC; ++a) {
         const int64_t tok = tok_base + (a * TILES + (4 * j) / GPAD) * 16 + n;
         float approx = 0.f;
+        int any_head = 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float x = acc[a][r] * p.scale;
@@ -266,14 +270,25 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
             const float mn = fmaxf(m[r], x);
             sum[r] = sum[r] * exp_fast(m[r] - mn) + exp_fast(x - mn);
             m[r] = mn;
-            if (FILTER) approx += exp_fast(x - fM[r]) * fInv[r];
+            if (FILTER) {
+              const float pr = exp_fast(x - fM[r]) * fInv[r];
+              approx += pr;
+              any_head |= !(pr < ftau_h[r]);
+            }
           }
         }
         if (FILTER) {
-          // the heads of a token sit in GPAD/4 lanes (same n, adjacent j): add their parts
-          if (GPAD >= 8) approx += __shfl_xor(approx, 16);
-          if (GPAD >= 16) approx += __shfl_xor(approx, 32);
-          const bool pass = tok >= p.filt.S && tok < L - p.filt.W && !(approx < ftau);
+          // the heads of a token sit in GPAD/4 lanes (same n, adjacent j): combine their parts
+          if (GPAD >= 8) {
+            approx += __shfl_xor(approx, 16);
+            any_head |= __shfl_xor(any_head, 16);
+          }
+          if (GPAD >= 16) {
+            approx += __shfl_xor(approx, 32);
+            any_head |= __shfl_xor(any_head, 32);
+          }
+          const bool reach = per_head ? any_head != 0 : !(approx < ftau);
+          const bool pass = tok >= p.filt.S && tok < L - p.filt.W && reach;
           const bool rep = (4 * j) % GPAD == 0;  // one lane per token counts it
           const unsigned long long bal = __ballot(pass && rep);
           if (bal) {  // wave-uniform
@@ -432,12 +447,14 @@ __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
         const float2 ss = p.samp_stats[(int64_t)row * p.G + g];
         const double r = exp((double)ss.x - (double)M) / (z * (double)ss.y);
         rho = r > rho || !(r == r) ? r : rho;
+        if (p.n_lists > 1)  // per-query lists: head g's own bound
+          p.bound[(int64_t)row * p.n_lists + g] = (float)(r * (double)p.samp_tau[(int64_t)row * p.n_lists + g] * 1.001);
       }
     }
   }
   // A token the filter dropped had approximate score < tau^; its exact score is below rho * tau^
   // (plus fp32 slack).  The candidate selection checks its threshold against this bound.
-  if (p.bound && lane == 0) p.bound[row] = (float)(rho * (double)p.samp_tau[row] * 1.001);
+  if (p.bound && p.n_lists == 1 && lane == 0) p.bound[row] = (float)(rho * (double)p.samp_tau[row] * 1.001);
 }
 
 constexpr int kCombineThreads = 256;

@@ -27,9 +27,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   __shared__ TopkShared sh;
   const int tid = threadIdx.x;
   int list = blockIdx.x;  // selection list: one per row (group-sum) or one per (row, query head)
-  if (p.gate.row_map) {   // gated launches are group-sum only: list = row
-    if ((int)blockIdx.x >= *p.gate.n_active) return;
-    list = p.gate.row_map[blockIdx.x];
+  if (p.gate.row_map) {
+    if ((int)blockIdx.x / p.n_lists >= *p.gate.n_active) return;
+    list = p.gate.row_map[blockIdx.x / p.n_lists] * p.n_lists + blockIdx.x % p.n_lists;
   }
   const int row = list / p.n_lists, gl = list % p.n_lists;
   const int g_lo = p.n_lists > 1 ? gl : 0, g_hi = p.n_lists > 1 ? gl + 1 : p.geo.G;

@@ -395,7 +395,7 @@ def test_C1_end_to_end(ref):
 
 
 # ----------------------------------------------------------------------------- per-query head mode (paper-literal)
-def per_query_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps, seed):
+def per_query_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps, seed, expect_fast=None):
     """Select with one top-k per query head, then decode steps where head g attends sink + its own
     list + recent (Sec. 2 Step 2, App. A.2)."""
     import torch
@@ -404,9 +404,14 @@ def per_query_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps, seed):
 
     G = Hq // Hkv
     q, K, V = rand_case(seed, P, Hq, Hkv, d, L, dtype)
-    out = gu.gpu_select(dtype, q, K, V, S, W, k, head_mode=1)
+    dense = gu.gpu_select(dtype, q, K, V, S, W, k, head_mode=1)
     Kc, Vc, kept, s = ref.select(dtype, 1, q, K, V, S, W, k, want_scores=True)  # s [P,Hkv,G,L]
-    gu.check_scores(out["scores"].reshape(P, Hkv, G, L), s)
+    gu.check_scores(dense["scores"].reshape(P, Hkv, G, L), s)
+    out = gu.gpu_select(dtype, q, K, V, S, W, k, head_mode=1, want_scores=False)  # pre-filtered where it applies
+    if expect_fast is not None:
+        assert (out["redone"] == 0) == expect_fast, out["redone"]
+    if np.array_equal(dense["kept"], kept):
+        np.testing.assert_array_equal(out["kept"], dense["kept"])
     n_kept = S + G * k + W
     assert out["kept"].shape[-1] == n_kept
     n_ex = 0
@@ -453,4 +458,10 @@ def test_per_query_paper_budget(ref):
     """The appendix's split for Llama (B = 8192, G = 4): sink 2048, 1024 per query head, recent 2048,
     on a 32K-token bf16 cache of two Llama-shaped layers."""
     sink, k, recent = ref.paper_budget(8192, 4)
-    per_query_case(ref, BF16, 2, 32, 8, 128, 32768, sink, recent, k, 2, seed=77)
+    per_query_case(ref, BF16, 2, 32, 8, 128, 32768, sink, recent, k, 2, seed=77, expect_fast=True)
+
+
+def test_per_query_prefiltered_G7(ref):
+    """Qwen-shaped group (G = 7) with the appendix's split of B = 8192 (2048 / 7 x 512 / 2560)."""
+    sink, k, recent = ref.paper_budget(8192, 7)
+    per_query_case(ref, BF16, 1, 14, 2, 128, 50000, sink, recent, k, 2, seed=78, expect_fast=True)
