@@ -225,6 +225,39 @@ def test_select_C2_shape_two_layers(ref):
         assert set(pos[r].tolist()) <= set(kept[r].tolist())
 
 
+def test_prefiltered_select_is_deterministic():
+    """The candidate lists are filled in whatever order the workgroups run; the result must not depend on it."""
+    q, K, V = rand_case(14, 2, 8, 2, 128, 40000, BF16)
+    first = gu.gpu_select(BF16, q, K, V, 4, 128, 1000, want_scores=False)
+    assert first["redone"] == 0
+    for _ in range(4):
+        again = gu.gpu_select(BF16, q, K, V, 4, 128, 1000, want_scores=False)
+        for name in ("kept", "Kc", "Vc"):
+            np.testing.assert_array_equal(first[name], again[name])
+
+
+def test_refresh_reselect_on_a_grown_cache(ref):
+    """Interval refresh (the paper's future work, Sec. 4): the full cache is kept in a buffer with
+    spare capacity, generated tokens are appended to it, and the eviction pass is run again with the
+    current token's query over the longer prefix, into the same reduced cache."""
+    import torch
+
+    P, Hq, Hkv, d, L0, Lcap, S, W, k = 1, 8, 2, 128, 30000, 30100, 4, 64, 600
+    q, K, V = rand_case(15, P, Hq, Hkv, d, Lcap, BF16)
+    Kd, Vd = synth.host_to_torch(K, BF16), synth.host_to_torch(V, BF16)
+    prev = None
+    for L in (L0, L0 + 37, Lcap):  # prefill, then two refreshes after 37 and 100 generated tokens
+        qL = synth.fill_host(synth.stream_key(15, 9), L, P * Hq * d, BF16).reshape(P, Hq, d)
+        out = gu.gpu_select(BF16, qL, None, None, S, W, k, want_scores=False, K_dev=Kd[:, :, :L], V_dev=Vd[:, :, :L])
+        Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, qL, np.ascontiguousarray(K[:, :, :L]),
+                                     np.ascontiguousarray(V[:, :, :L]), S, W, k, want_scores=True)
+        assert gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k) == 0
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
+        assert prev is None or not np.array_equal(prev, out["kept"])
+        prev = out["kept"]
+
+
 # ----------------------------------------------------------------------------- error paths (host checks only)
 def test_invalid_arguments_are_rejected_before_launch():
     import torch
