@@ -320,6 +320,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
       const int t_local = i * TPL + tq;
       float vf[EPL];
       unpack16<DT_BF16>(vv[i], vf);
+      if (more) {  // the register is free: V of the next block, as early as possible
+        const int tokn = t_begin + (b + NW) * BT + i * TPL + tq;
+        const int tcn = tokn < t_end ? tokn : t_begin;
+        const char* src = (tcn == slot) ? vn : Vr + (int64_t)tcn * ROWB;
+        vv[i] = STREAM ? ld16_stream(src + cl * 16) : ld16(src + cl * 16);
+      }
 #pragma unroll
       for (int g4 = 0; g4 < GPAD / 4; ++g4) {
         const float4 p4 = *reinterpret_cast<const float4*>(&pbuf[wave][t_local][g4 * 4]);
@@ -330,7 +336,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
           for (int e = 0; e < EPL; ++e) acc[g4 * 4 + r][e] = fmaf(pp[r], vf[e], acc[g4 * 4 + r][e]);
       }
     }
-    if (more) load_block(b + NW, vv, Vr, vn);
   }
 
   // wave totals: sum of weights per head, accumulators over the TPL token groups
