@@ -447,12 +447,15 @@ hipError_t launch_decode_g(const DecodeParams& p, int g0, int gb, dim3 grid, hip
 
 template <int D, bool STREAM>
 hipError_t launch_decode_mfma_s(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
-  const bool single = p.n_splits == 1;  // one workgroup per row: 8 waves, else 4
+  // Workgroup size.  A row split over several workgroups: 4 waves.  One workgroup per row: 8 waves, one
+  // workgroup per CU (for 256 < rows <= 512, 4-wave workgroups that are all resident at once were
+  // measured no faster than two rounds of 8-wave ones).
+  const bool big = p.n_splits == 1;
   if (gb <= 4) {
-    if (single) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
     else hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   } else {
-    if (single) hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
     else hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   }
   return hipGetLastError();
