@@ -166,6 +166,19 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
   const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
   const int64_t tok_bytes = p.ks_token * 2;
 
+  // The waves of a workgroup take the chunk's 64-token blocks round robin, so the workgroup reads
+  // one contiguous 64 KiB run at a time; the first block's loads go out before anything else.
+  const int64_t wave_base = (int64_t)blockIdx.x * kScoreChunk + (int64_t)wave * 64;
+  constexpr int64_t kBlockStride = 64 * kScoreWaves;
+  uint4 kv[NLOAD];
+  if (wave_base < L) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      int64_t tok = wave_base + i * TPL + tq;
+      tok = tok < L ? tok : L - 1;  // tail: re-read the last token, masked below
+      kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
+    }
+  }
   // A operand: lane (row m = n, k-group j) holds q[head m % GPAD][8*(4*kc + j) ..+8]
   const int my_head = n % GPAD, my_slot = n / GPAD;
   uint4 qa[KSTEPS];
@@ -210,20 +223,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
   // their latency overlaps block b's MFMA phase.  The logits stay in registers until the wave
   // has loaded its last block: loads and stores share one in-order completion counter, so a
   // store inside the loop would put its write-ack latency on the critical path of every block.
-  const int64_t wave_base = (int64_t)blockIdx.x * kScoreChunk + (int64_t)wave * kBlocksPerWave * 64;
-  uint4 kv[NLOAD];
-  if (wave_base < L) {
-#pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-      int64_t tok = wave_base + i * TPL + tq;
-      tok = tok < L ? tok : L - 1;  // tail: re-read the last token, masked below
-      kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
-    }
-  }
   float xs[FILTER ? 1 : kBlocksPerWave][NACC][4];
 #pragma unroll
   for (int blk = 0; blk < kBlocksPerWave; ++blk) {
-    const int64_t tok_base = wave_base + (int64_t)blk * 64;
+    const int64_t tok_base = wave_base + (int64_t)blk * kBlockStride;
     if (tok_base < L) {  // wave-uniform
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // previous block's LDS reads are done
 #pragma unroll
@@ -232,10 +235,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
         buf[t * CH + (cl ^ (t & (CH - 1)))] = kv[i];
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      if (blk + 1 < kBlocksPerWave && tok_base + 64 < L) {
+      if (blk + 1 < kBlocksPerWave && tok_base + kBlockStride < L) {
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-          int64_t tok = tok_base + 64 + i * TPL + tq;
+          int64_t tok = tok_base + kBlockStride + i * TPL + tq;
           tok = tok < L ? tok : L - 1;
           kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
         }
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
   for (int blk = 0; blk < (FILTER ? 0 : kBlocksPerWave); ++blk) {
 #pragma unroll
     for (int a = 0; a < NACC; ++a) {
-      const int64_t tok = wave_base + (int64_t)blk * 64 + (a * TILES + (4 * j) / GPAD) * 16 + n;
+      const int64_t tok = wave_base + (int64_t)blk * kBlockStride + (a * TILES + (4 * j) / GPAD) * 16 + n;
 #pragma unroll
       for (int r = 0; r < 4; ++r)
         if (tok < L && hbase + r < gb)
