@@ -47,6 +47,16 @@ def read_traffic(cfg_name):
     return float(m.group(1)) if m else None
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
     """Times the CPU oracle, as it stands, on the first n_layers layers of the same workload: the
     eviction pass repeated for about select_seconds, then decode steps for about decode_seconds."""
@@ -76,6 +86,15 @@ def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
         ref.decode_attn(sub.dtype, ref.GROUP_SUM, qs, Kc, Vc, sub.budget)
         t_dec += time.perf_counter() - t0
         n_dec += 1
+    # one row = one oracle thread (its only parallel loop is over rows)
+    one = sub.with_(n_layers=1, batch=1)
+    K1 = np.ascontiguousarray(K[:1, :1])
+    V1 = np.ascontiguousarray(V[:1, :1])
+    q1 = np.ascontiguousarray(q[:1, : sub.G])
+    t0 = time.perf_counter()
+    ref.select(sub.dtype, ref.GROUP_SUM, q1, K1, V1, sub.n_sink, sub.n_recent, sub.k)
+    t_one = time.perf_counter() - t0
+    one_row_bytes = algorithmic_bytes(one)[0] // one.n_kv_heads
     sel_b, dec_b, _ = algorithmic_bytes(sub)
     # same mix as a bench step: one eviction pass + cfg.decode_steps decode steps
     t_step = t_sel / n_sel + cfg.decode_steps * t_dec / n_dec
@@ -84,6 +103,8 @@ def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
         "unit": "GB/s",
         "cores": ref.threads(),
         "kind": "oracle",
+        "cpu_model": cpu_model(),
+        "select_GBps_one_thread": one_row_bytes / t_one / 1e9,
         "sample": f"first {n_layers} of {cfg.n_layers} layers ({sub.rows} rows of L={cfg.L}): eviction pass x{n_sel} "
                   f"({t_sel:.1f} s), {n_dec} decode steps ({t_dec:.1f} s); value = bytes of (1 pass + "
                   f"{cfg.decode_steps} steps) on these layers / their time",
@@ -93,10 +114,49 @@ def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
     }, kept
 
 
+def layer_sequential(sk, torch, cfg, head_mode, Bt, q_steps, kn_steps, vn_steps, Kc, Vc, out, n_steps):
+    """Decode in the dependency order of a real model: one call per layer (its batch x KV heads
+    rows only), layers one after the other.  Timed eagerly (one library call per layer from
+    Python) and as one HIP graph of the same calls.  Reported beside the headline, never as it."""
+    lb = cfg.batch
+    ldesc = sk.decode_desc(lb, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.dtype, cfg.n_sink, cfg.k,
+                           cfg.n_recent, Bt, head_mode=head_mode)
+    lws = torch.empty(max(sk.sagekv_decode_workspace_bytes(ldesc), 16), dtype=torch.uint8, device="cuda")
+
+    def run():
+        for t in range(n_steps):
+            for l in range(cfg.n_layers):
+                sl = slice(l * lb, (l + 1) * lb)
+                sk.sagekv_decode_step(ldesc, q_steps[t][sl], kn_steps[t][sl], vn_steps[t][sl], Kc[sl], Vc[sl], t,
+                                      out[sl], lws)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_steps
+
+    res = {"steps": n_steps, "launches_per_token": cfg.n_layers}
+    ms = timed(run)
+    res["eager_ms_per_token"] = round(ms, 4)
+    res["eager_tokens_per_s"] = round(cfg.batch / (ms * 1e-3), 1)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    ms = timed(graph.replay)
+    res["graph_ms_per_token"] = round(ms, 4)
+    res["graph_tokens_per_s"] = round(cfg.batch / (ms * 1e-3), 1)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="C3", help="C2, C3 (default: the 128K Llama-3.1-8B-shaped target), C4, C5")
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per step (default: the config's)")
@@ -107,6 +167,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, run one plain 1 GiB device-to-device copy (a reference of "
                          "known size for rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--layer-sequential-steps", type=int, default=8,
+                    help="decode steps of the untimed-in-value extra figure that launches one layer at a time")
     ap.add_argument("--cpu-layers", type=int, default=2)
     ap.add_argument("--cpu-select-seconds", type=float, default=10.0)
     ap.add_argument("--cpu-decode-seconds", type=float, default=5.0)
@@ -192,8 +254,9 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    sel_all = [e[0].elapsed_time(e[1]) for e in events]
+    dec_all = [e[1].elapsed_time(e[2]) for e in events]
+    sel_ms, dec_ms = float(np.mean(sel_all)), float(np.mean(dec_all))
     stage_ms = np.array([sk.sagekv_stage_timing_read(0, i) for i in range(args.steps)]).mean(axis=0)
     n_dec_timed = min(args.steps, max(n_dec * args.steps, 0))
     dec_kernel_ms = float(np.mean([sk.sagekv_stage_timing_read(1, i)[0] for i in range(n_dec_timed)])) if n_dec else None
@@ -231,11 +294,12 @@ def main():
             "step": "1 eviction pass over the whole cache + the decode steps",
         },
         "frac_hbm": round(value / HBM_PEAK_GBPS, 4),
-        "select": {"ms": round(sel_ms, 4), "GBps": round(sel_gbps, 1), "frac_hbm": round(sel_gbps / HBM_PEAK_GBPS, 4),
+        "select": {"ms": round(sel_ms, 4), "ms_median": round(float(np.median(sel_all)), 4), "GBps": round(sel_gbps, 1), "frac_hbm": round(sel_gbps / HBM_PEAK_GBPS, 4),
                    "algorithmic_bytes": sel_b, "rows_redone_by_dense_path": redone,
                    "stage_ms": {n: round(float(v), 4) for n, v in zip(sk.binding.STAGES, stage_ms)}},
         "decode": {"tokens_per_s": None if dec_tok_s is None else round(dec_tok_s, 1),
                    "ms_per_token": None if not n_dec else round(dec_ms / n_dec, 5),
+                   "ms_per_token_median": None if not n_dec else round(float(np.median(dec_all)) / n_dec, 5),
                    "GBps": None if dec_gbps is None else round(dec_gbps, 1),
                    "frac_hbm": None if dec_gbps is None else round(dec_gbps / HBM_PEAK_GBPS, 4),
                    "kernel_ms": None if dec_kernel_ms is None else round(dec_kernel_ms, 5),
@@ -244,6 +308,10 @@ def main():
                      "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(score_ms, 4),
                      "algorithmic_bytes": score_b, "traffic": read_traffic(cfg.name)},
     }
+    if n_dec and args.layer_sequential_steps > 0:
+        result["decode"]["layer_sequential"] = layer_sequential(
+            sk, torch, cfg, head_mode, Bt, q_steps, kn_steps, vn_steps, Kc, Vc, out,
+            min(n_dec, args.layer_sequential_steps))
     if not args.no_cpu_baseline:
         base, kept_ref = cpu_baseline(cfg, args.cpu_layers, args.cpu_select_seconds, args.cpu_decode_seconds)
         # free check: the sampled layers' kept sets must be the oracle's
