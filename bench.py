@@ -163,6 +163,8 @@ def main():
     ap.add_argument("--per-query-budget", type=int, default=0, metavar="B",
                     help="paper-literal head mode: one top-k per query head with the appendix's split of a token "
                          "budget B (sink B/4, k = pow2floor(B/2G) per head, recent = rest) instead of the config's")
+    ap.add_argument("--page-size", type=int, default=0, metavar="T",
+                    help="hold K and V in shuffled pages of T tokens (block-table layout) and run the paged entry point")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, run one plain 1 GiB device-to-device copy (a reference of "
@@ -211,8 +213,29 @@ def main():
     synth.fill_device(kn_steps, synth.stream_key(cfg.seed, synth.T_KNEW))
     synth.fill_device(vn_steps, synth.stream_key(cfg.seed, synth.T_VNEW))
 
+    pages = None
+    if args.page_size:
+        ps = args.page_size
+        assert cfg.L % ps == 0, "bench pages must divide L"
+        per = cfg.L // ps
+        gen = torch.Generator(device="cpu").manual_seed(cfg.seed)
+        perm = torch.randperm(P * per, generator=gen).to(dev)
+        table = perm.to(torch.int32).view(P, per).contiguous()
+
+        def paged(X):
+            src = X.view(P, Hkv, per, ps, d).permute(0, 2, 1, 3, 4).reshape(P * per, Hkv, ps, d)
+            pool = torch.empty_like(src)
+            pool[perm] = src
+            return pool
+
+        K, V = paged(K), paged(V)
+        torch.cuda.synchronize()
+
     # ---- outputs and workspaces (allocated once, outside the timed region)
-    sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt, head_mode=head_mode)
+    if args.page_size:
+        sdesc, pages = sk.paged_select_desc(q_last, K, V, table, cfg.L, S, W, k, Bt, head_mode=head_mode)
+    else:
+        sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt, head_mode=head_mode)
     sws = torch.empty(sk.sagekv_select_workspace_bytes(sdesc), dtype=torch.uint8, device=dev)
     Kc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
     Vc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
@@ -224,7 +247,10 @@ def main():
     def one_step(ev=None):
         if ev:
             ev[0].record()
-        sk.sagekv_select(sdesc, q_last, K, V, Kc, Vc, kept, None, sws)
+        if pages is not None:
+            sk.sagekv_select_paged(sdesc, pages, q_last, K, V, Kc, Vc, kept, None, sws)
+        else:
+            sk.sagekv_select(sdesc, q_last, K, V, Kc, Vc, kept, None, sws)
         if ev:
             ev[1].record()
         for t in range(n_dec):
@@ -289,7 +315,8 @@ def main():
         "config": {
             "workload": f"{cfg.name}: {cfg.n_layers} layers x batch {cfg.batch}, {Hq}q/{Hkv}kv heads, head_dim {d}, "
                         f"L={cfg.L}, budget {Bt} = {S} sink + {lists}x{k} top-k + {W} recent, {n_dec} decode steps per step"
-                        + (", one top-k per query head" if lists > 1 else ""),
+                        + (", one top-k per query head" if lists > 1 else "")
+                        + (f", K and V in shuffled pages of {args.page_size} tokens" if args.page_size else ""),
             "rows": cfg.rows,
             "step": "1 eviction pass over the whole cache + the decode steps",
         },
@@ -315,7 +342,7 @@ def main():
     if not args.no_cpu_baseline:
         base, kept_ref = cpu_baseline(cfg, args.cpu_layers, args.cpu_select_seconds, args.cpu_decode_seconds)
         # free check: the sampled layers' kept sets must be the oracle's
-        sk.sagekv_select(sdesc, q_last, K, V, Kc, Vc, kept, None, sws)
+        one_step()
         torch.cuda.synchronize()
         got = kept[: kept_ref.shape[0]].cpu().numpy()
         base["kept_sets_equal_oracle_rows"] = int((got == kept_ref).all(axis=-1).sum())

@@ -104,6 +104,28 @@ sagekv_status sagekv_select(const sagekv_select_desc* desc, const void* q_last, 
                             void* Kc, void* Vc, int32_t* kept_idx, float* scores_out, void* workspace,
                             size_t workspace_bytes, void* hip_stream);
 
+/* Paged caches (the block-table layout of serving engines; Sec. 2 Step 1 only fixes WHICH tokens
+ * form the cache, not where they live).  The tokens of a problem are cut into logical pages of
+ * page_size tokens; logical page j of problem p is physical page block_table[p * table_pitch + j]
+ * of a pool, and token t of KV head c sits at
+ *   pool + page * k_stride_page + c * k_stride_head + (t mod page_size) * k_stride_token   (elements),
+ * with desc->k_stride_head / k_stride_token (v_*) now meaning the strides INSIDE a page;
+ * desc->k_stride_problem / v_stride_problem are ignored.  All pointers are device pointers. */
+typedef struct sagekv_paged_kv {
+  const int32_t* block_table; /* [n_problems][table_pitch], entries in [0, n_pages) (clamped to it) */
+  int64_t table_pitch;        /* >= ceil(L / page_size) */
+  int32_t page_size;          /* tokens per page: a power of two, >= 16 */
+  int32_t n_pages;            /* pages in the pool */
+  int64_t k_stride_page;      /* elements, multiple of 16 bytes */
+  int64_t v_stride_page;
+} sagekv_paged_kv;
+
+/* sagekv_select over a paged cache: same selection, same outputs (Kc, Vc dense as above), same
+ * workspace size.  K_pool / V_pool are the page pools. */
+sagekv_status sagekv_select_paged(const sagekv_select_desc* desc, const sagekv_paged_kv* pages, const void* q_last,
+                                  const void* K_pool, const void* V_pool, void* Kc, void* Vc, int32_t* kept_idx,
+                                  float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Test / benchmark aid: waits for the stream, then reports how many rows of the LAST sagekv_select
  * call that used this workspace were redone by the dense path (-1 if the call was dense anyway).
  * `n_rows` is a host pointer. */

@@ -18,7 +18,8 @@ STAGES = ("sample", "score", "stats", "combine", "topk", "redo", "gather")
 SELECT_DENSE = 1
 
 EXPORTS = (
-    "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_select_redone_rows",
+    "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_select_paged",
+    "sagekv_select_redone_rows",
     "sagekv_append",
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read",
@@ -34,6 +35,13 @@ class SelectDesc(ctypes.Structure):
         ("v_stride_problem", ctypes.c_int64), ("v_stride_head", ctypes.c_int64), ("v_stride_token", ctypes.c_int64),
         ("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32), ("k", ctypes.c_int32),
         ("compact_capacity", ctypes.c_int32), ("flags", ctypes.c_uint32),
+    ]
+
+
+class PagedKV(ctypes.Structure):
+    _fields_ = [
+        ("block_table", ctypes.c_void_p), ("table_pitch", ctypes.c_int64), ("page_size", ctypes.c_int32),
+        ("n_pages", ctypes.c_int32), ("k_stride_page", ctypes.c_int64), ("v_stride_page", ctypes.c_int64),
     ]
 
 
@@ -69,6 +77,9 @@ def lib():
         L.sagekv_select_workspace_bytes.argtypes = [ctypes.POINTER(SelectDesc)]
         L.sagekv_select.restype = ctypes.c_int
         L.sagekv_select.argtypes = [ctypes.POINTER(SelectDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.sagekv_select_paged.restype = ctypes.c_int
+        L.sagekv_select_paged.argtypes = [ctypes.POINTER(SelectDesc), ctypes.POINTER(PagedKV), vp, vp, vp, vp, vp, vp, vp,
+                                          vp, sz, vp]
         L.sagekv_select_redone_rows.restype = ctypes.c_int
         L.sagekv_select_redone_rows.argtypes = [ctypes.POINTER(SelectDesc), vp, sz, vp, ctypes.POINTER(i32)]
         L.sagekv_append.restype = ctypes.c_int
@@ -138,6 +149,34 @@ def sagekv_select(desc: SelectDesc, q_last, K, V, Kc, Vc, kept_idx, scores_out, 
                                _ptr(kept_idx), _ptr(scores_out), _ptr(workspace),
                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(code, "sagekv_select")
+
+
+def paged_select_desc(q_last, K_pool, V_pool, block_table, L, n_sink, n_recent, k, compact_capacity=None,
+                      head_mode=GROUP_SUM, flags=0):
+    """Descriptors for q_last [P,Hq,d], page pools K_pool, V_pool [n_pages, Hkv, page_size, d] (any strides
+    with a unit inner stride) and block_table [P, pages_per_problem] int32.  Returns (SelectDesc, PagedKV)."""
+    import torch
+
+    P, Hq, d = q_last.shape
+    n_pages, Hkv, page_size, _ = K_pool.shape
+    assert K_pool.stride(3) == 1 and V_pool.stride(3) == 1 and q_last.is_contiguous()
+    assert block_table.dtype == torch.int32 and block_table.shape[0] == P and block_table.stride(1) == 1
+    lists = Hq // Hkv if head_mode == PER_QUERY else 1
+    cap = n_sink + lists * k + n_recent if compact_capacity is None else compact_capacity
+    desc = SelectDesc(P, Hq, Hkv, d, _dtype_of(K_pool), head_mode, L, 0, K_pool.stride(1), K_pool.stride(2),
+                      0, V_pool.stride(1), V_pool.stride(2), n_sink, n_recent, k, cap, flags)
+    pages = PagedKV(block_table.data_ptr(), block_table.stride(0), page_size, n_pages, K_pool.stride(0),
+                    V_pool.stride(0))
+    return desc, pages
+
+
+def sagekv_select_paged(desc: SelectDesc, pages: PagedKV, q_last, K_pool, V_pool, Kc, Vc, kept_idx, scores_out,
+                        workspace) -> None:
+    """sagekv_select over a paged cache (block table + page pools)."""
+    code = lib().sagekv_select_paged(ctypes.byref(desc), ctypes.byref(pages), _ptr(q_last), _ptr(K_pool), _ptr(V_pool),
+                                     _ptr(Kc), _ptr(Vc), _ptr(kept_idx), _ptr(scores_out), _ptr(workspace),
+                                     _ws_bytes(workspace), _stream())
+    _check(code, "sagekv_select_paged")
 
 
 def sagekv_select_redone_rows(desc: SelectDesc, workspace) -> int:

@@ -286,9 +286,13 @@ size_t sagekv_select_workspace_bytes(const sagekv_select_desc* desc) {
   return select_layout(desc, true).total;
 }
 
-sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, const void* K, const void* V, void* Kc,
-                            void* Vc, int32_t* kept_idx, float* scores_out, void* workspace, size_t workspace_bytes,
-                            void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const void* q_last, const void* K,
+                          const void* V, void* Kc, void* Vc, int32_t* kept_idx, float* scores_out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
   sagekv_status st;
   if (!check_select(d, &st)) return st;
   if (!q_last || !K || !V || !Kc || !Vc || !kept_idx) return SAGEKV_ERR_INVALID_ARG;
@@ -328,6 +332,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   sp.ks_problem = d->k_stride_problem;
   sp.ks_head = d->k_stride_head;
   sp.ks_token = d->k_stride_token;
+  sp.pm = pm;
   sp.logits = logits;
   sp.partials = partials;
   sp.n_chunks = l.n_chunks;
@@ -360,6 +365,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
     mp.ks_problem = d->k_stride_problem;
     mp.ks_head = d->k_stride_head;
     mp.ks_token = d->k_stride_token;
+    mp.pm = pm;
     mp.S = d->n_sink;
     mp.W = d->n_recent;
     mp.k = d->k;
@@ -428,6 +434,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
     cp.ks_problem = d->k_stride_problem;
     cp.ks_head = d->k_stride_head;
     cp.ks_token = d->k_stride_token;
+    cp.pm = pm;
     cp.kept_idx = kept_idx;
     cp.row_fail = row_fail;
     cp.S = d->n_sink;
@@ -487,6 +494,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   kp.ks_problem = d->k_stride_problem;
   kp.ks_head = d->k_stride_head;
   kp.ks_token = d->k_stride_token;
+  kp.pm = pm;
   kp.kept_idx = kept_idx;
   kp.S = d->n_sink;
   kp.W = d->n_recent;
@@ -509,6 +517,7 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   gp.vs_problem = d->v_stride_problem;
   gp.vs_head = d->v_stride_head;
   gp.vs_token = d->v_stride_token;
+  gp.pm = pm;
   gp.kept_idx = kept_idx;
   gp.Kc = Kc;
   gp.Vc = Vc;
@@ -518,6 +527,40 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   e = launch_gather(gp, s);
   t.end(SAGEKV_STAGE_GATHER);
   return dev(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, const void* K, const void* V, void* Kc,
+                            void* Vc, int32_t* kept_idx, float* scores_out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  const PageMap none = {nullptr, 0, 0, 0, 0, 0};
+  return select_impl(d, none, q_last, K, V, Kc, Vc, kept_idx, scores_out, workspace, workspace_bytes, hip_stream);
+}
+
+sagekv_status sagekv_select_paged(const sagekv_select_desc* d, const sagekv_paged_kv* pg, const void* q_last,
+                                  const void* K_pool, const void* V_pool, void* Kc, void* Vc, int32_t* kept_idx,
+                                  float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_select(d, &st)) return st;
+  if (!pg || !pg->block_table || pg->n_pages < 1) return SAGEKV_ERR_INVALID_ARG;
+  const int ps = pg->page_size;
+  if (ps < 16 || (ps & (ps - 1))) return SAGEKV_ERR_INVALID_ARG;
+  if (pg->table_pitch < (d->L + ps - 1) / ps) return SAGEKV_ERR_INVALID_ARG;
+  const int epl = d->dtype == SAGEKV_BF16 ? 8 : 4;
+  if (pg->k_stride_page < 0 || pg->v_stride_page < 0 || pg->k_stride_page % epl || pg->v_stride_page % epl)
+    return SAGEKV_ERR_UNSUPPORTED;
+  PageMap pm;
+  pm.table = pg->block_table;
+  pm.pitch = pg->table_pitch;
+  pm.ks_page = pg->k_stride_page;
+  pm.vs_page = pg->v_stride_page;
+  pm.shift = __builtin_ctz((unsigned)ps);
+  pm.n_pages = pg->n_pages;
+  return select_impl(d, pm, q_last, K_pool, V_pool, Kc, Vc, kept_idx, scores_out, workspace, workspace_bytes,
+                     hip_stream);
 }
 
 sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* d, const void* workspace, size_t workspace_bytes,

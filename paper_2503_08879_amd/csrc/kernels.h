@@ -24,6 +24,31 @@ struct RowGeom {
   int64_t Lp;  // pitch (floats) of the logit rows, multiple of 4
 };
 
+// Paged caches.  table = nullptr: the cache is one strided array and token t of (problem, head)
+// sits at problem * s_problem + head * s_head + t * s_token (elements).  Otherwise a row's tokens
+// are cut into pages of 2^shift tokens and page j of a problem is physical page
+// table[problem * pitch + j] of a pool: page * s_page + head * s_head + (t mod 2^shift) * s_token.
+// Table entries are clamped to [0, n_pages) before use.
+struct PageMap {
+  const int32_t* table;
+  int64_t pitch;
+  int64_t ks_page, vs_page;  // elements between pages of the K pool, of the V pool
+  int shift;
+  int n_pages;
+};
+
+__device__ __forceinline__ int page_of(const PageMap& pm, int prob, int64_t tok) {
+  const int pid = pm.table[(int64_t)prob * pm.pitch + (tok >> pm.shift)];
+  return pid < 0 ? 0 : (pid >= pm.n_pages ? pm.n_pages - 1 : pid);
+}
+
+// Element offset of token tok of (prob, head c) in K (or, with the V strides, in V).
+__device__ __forceinline__ int64_t kv_offset(const PageMap& pm, int64_t s_page, int64_t s_problem, int64_t s_head,
+                                             int64_t s_token, int prob, int c, int64_t tok) {
+  if (!pm.table) return (int64_t)prob * s_problem + (int64_t)c * s_head + tok * s_token;
+  return (int64_t)page_of(pm, prob, tok) * s_page + (int64_t)c * s_head + (tok & ((1 << pm.shift) - 1)) * s_token;
+}
+
 // Rows a gated launch works on: row = row_map[blockIdx] while blockIdx < *n_active (both device
 // memory).  Null row_map = all rows, identity.
 struct RowGate {
@@ -54,6 +79,7 @@ struct ScoreParams {
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;  // elements
+  PageMap pm;
   float* logits;                          // [rows][n_chunks][G][kScoreChunk]
   float2* partials;                       // [rows][G][n_chunks]  (max, sum exp(x - max))
   int n_chunks;
@@ -97,6 +123,7 @@ struct TopkParams {
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;
+  PageMap pm;
   int32_t* kept_idx;  // [rows][S + n_lists * k + W]
   int S, W, k;
   int n_lists;        // 1 or G; list g of a row ranks head g's own probabilities
@@ -112,6 +139,7 @@ struct SampleParams {
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;
+  PageMap pm;
   int S, W, k;
   int nA, nB, nC;       // blocks per part
   int64_t stepB;        // 48.16 fixed-point distance between the starts of the 16-token candidate runs
@@ -153,6 +181,7 @@ struct TopkCandParams {
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;
+  PageMap pm;
   int32_t* kept_idx;
   int* row_fail;  // set to 1 when the row must be redone by the general path
   int S, W, k;
@@ -164,6 +193,7 @@ struct GatherParams {
   const void* K;
   const void* V;
   int64_t ks_problem, ks_head, ks_token, vs_problem, vs_head, vs_token;
+  PageMap pm;
   const int32_t* kept_idx;
   void* Kc;
   void* Vc;

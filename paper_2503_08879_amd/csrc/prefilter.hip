@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   }
   for (int t = tid >> 6; t < nb; t += kTopkWaves) {
     const int tok = ci[band_j[t]];
-    const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c,
+    const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c,
                                            row, tok, g_lo, g_hi);
     if ((tid & 63) == 0) {
       band_v[t] = v;

@@ -85,11 +85,11 @@ __device__ inline double elem_f64<DT_F32>(const void* base, int64_t i) {
 
 // Score of token `tok` of the row in fp64 (heads g_lo .. g_hi-1 of the group), rounded once to fp32.
 template <int DT>
-__device__ inline float refined_score(const RowGeom& geo, const void* q_last, const void* K, int64_t ks_problem,
-                                   int64_t ks_head, int64_t ks_token, const RowStat* stats, int prob, int c, int row,
-                                   int64_t tok, int g_lo, int g_hi) {
+__device__ inline float refined_score(const RowGeom& geo, const void* q_last, const void* K, const PageMap& pm,
+                                   int64_t ks_problem, int64_t ks_head, int64_t ks_token, const RowStat* stats,
+                                   int prob, int c, int row, int64_t tok, int g_lo, int g_hi) {
   const int D = geo.D, G = geo.G;
-  const int64_t k_off = (int64_t)prob * ks_problem + (int64_t)c * ks_head + tok * ks_token;
+  const int64_t k_off = kv_offset(pm, pm.ks_page, ks_problem, ks_head, ks_token, prob, c, tok);
   const double inv = 1.0 / sqrt((double)D);
   double tot = 0.0;
   for (int g = g_lo; g < g_hi; ++g) {
@@ -105,11 +105,11 @@ __device__ inline float refined_score(const RowGeom& geo, const void* q_last, co
 // The same value computed by one whole wave: lanes split head_dim, fp64 tree reduction (the fp64
 // sum order differs from the sequential one by ~1e-16 relative, far below fp32 rounding).
 template <int DT>
-__device__ inline float refined_score_wave(const RowGeom& geo, const void* q_last, const void* K, int64_t ks_problem,
-                                        int64_t ks_head, int64_t ks_token, const RowStat* stats, int prob, int c,
-                                        int row, int64_t tok, int g_lo, int g_hi) {
+__device__ inline float refined_score_wave(const RowGeom& geo, const void* q_last, const void* K, const PageMap& pm,
+                                        int64_t ks_problem, int64_t ks_head, int64_t ks_token, const RowStat* stats,
+                                        int prob, int c, int row, int64_t tok, int g_lo, int g_hi) {
   const int D = geo.D, G = geo.G, lane = threadIdx.x & 63;
-  const int64_t k_off = (int64_t)prob * ks_problem + (int64_t)c * ks_head + tok * ks_token;
+  const int64_t k_off = kv_offset(pm, pm.ks_page, ks_problem, ks_head, ks_token, prob, c, tok);
   const double inv = 1.0 / sqrt((double)D);
   double tot = 0.0;
   for (int g = g_lo; g < g_hi; ++g) {

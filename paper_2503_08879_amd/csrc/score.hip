@@ -46,9 +46,6 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
   const int tq = lane / LPT, cl = lane % LPT;
   const int64_t L = p.geo.L;
 
-  const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * EB;
-  const int64_t tok_bytes = p.ks_token * EB;
-
   uint4 q[GB];
 #pragma unroll
   for (int g = 0; g < GB; ++g) {
@@ -77,7 +74,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
       for (int i = 0; i < SB; ++i) {
         int64_t tok = tok_base + (i0 + i) * TPL + tq;
         tok = tok < L ? tok : L - 1;  // tail: re-read the last token, masked below
-        kv[i] = ld16(Krow + tok * tok_bytes + cl * 16);
+        const int64_t off = kv_offset(p.pm, p.pm.ks_page, p.ks_problem, p.ks_head, p.ks_token, prob, c, tok);
+        kv[i] = ld16((const char*)p.K + off * EB + cl * 16);
       }
 #pragma unroll
       for (int i = 0; i < SB; ++i) {
@@ -138,7 +136,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
 // FILTER = true is the fast eviction path: nothing is written per token.  A lane keeps its logits
 // only for tokens whose approximate score (sample statistics) reaches the row's conservative
 // threshold, and appends (index, logits) to the row's candidate list.
-template <int D, int GPAD, bool FILTER>
+//
+// PAGED: the chunk's pages (at most 64: pages hold 16 tokens or more) are looked up once, one per
+// lane, and every load takes its page from the lane that holds it.
+template <int D, int GPAD, bool FILTER, bool PAGED>
 __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p, int gb) {
   constexpr int CH = D / 8;         // 16-byte chunks per token
   constexpr int TPL = 64 / CH;      // tokens per coalesced wave load
@@ -165,6 +166,22 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
 
   const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
   const int64_t tok_bytes = p.ks_token * 2;
+  int my_page = 0, first_page = 0;
+  if (PAGED) {
+    Krow = (const char*)p.K + (int64_t)c * p.ks_head * 2;
+    first_page = (int)(((int64_t)blockIdx.x * kScoreChunk) >> p.pm.shift);
+    const int last_page = (int)((L - 1) >> p.pm.shift);
+    const int pg = first_page + lane < last_page ? first_page + lane : last_page;
+    my_page = page_of(p.pm, prob, (int64_t)pg << p.pm.shift);
+  }
+  // address of this lane's 16 bytes of token tok (every lane of the wave calls it together)
+  auto k_addr = [&](int64_t tok) -> const char* {
+    if (PAGED) {
+      const int pid = __shfl(my_page, (int)(tok >> p.pm.shift) - first_page);
+      return Krow + ((int64_t)pid * p.pm.ks_page * 2 + (tok & ((1 << p.pm.shift) - 1)) * tok_bytes) + cl * 16;
+    }
+    return Krow + tok * tok_bytes + cl * 16;
+  };
 
   // The waves of a workgroup take the chunk's 64-token blocks round robin, so the workgroup reads
   // one contiguous 64 KiB run at a time; the first block's loads go out before anything else.
@@ -176,7 +193,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
     for (int i = 0; i < NLOAD; ++i) {
       int64_t tok = wave_base + i * TPL + tq;
       tok = tok < L ? tok : L - 1;  // tail: re-read the last token, masked below
-      kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
+      kv[i] = ld16_stream(k_addr(tok));
     }
   }
   // A operand: lane (row m = n, k-group j) holds q[head m % GPAD][8*(4*kc + j) ..+8]
@@ -240,7 +257,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
         for (int i = 0; i < NLOAD; ++i) {
           int64_t tok = tok_base + kBlockStride + i * TPL + tq;
           tok = tok < L ? tok : L - 1;
-          kv[i] = ld16_stream(Krow + tok * tok_bytes + cl * 16);
+          kv[i] = ld16_stream(k_addr(tok));
         }
       }
       f32x4_t acc[NACC];
@@ -369,15 +386,13 @@ __global__ __launch_bounds__(kScoreThreads) void sample_logits_kernel(SamplePara
   const int blk = blockIdx.x * kScoreWaves + wave;
   if (blk >= p.nA + p.nB + p.nC) return;  // wave-uniform; no workgroup barrier below
   uint4* buf = lds[wave];
-  const char* Krow = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * 2;
-  const int64_t tok_bytes = p.ks_token * 2;
-
   uint4 kv[NLOAD];
 #pragma unroll
   for (int i = 0; i < NLOAD; ++i) {
     int64_t tok = sample_token(p, blk, i * TPL + tq);
     tok = tok < 0 ? 0 : (tok < L ? tok : L - 1);
-    kv[i] = ld16(Krow + tok * tok_bytes + cl * 16);
+    const int64_t off = kv_offset(p.pm, p.pm.ks_page, p.ks_problem, p.ks_head, p.ks_token, prob, c, tok);
+    kv[i] = ld16((const char*)p.K + off * 2 + cl * 16);
   }
   const int my_head = n % GPAD, my_slot = n / GPAD;
   uint4 qa[KSTEPS];
@@ -539,15 +554,21 @@ hipError_t launch_score_g(const ScoreParams& p, int gb, dim3 grid, hipStream_t s
   return hipGetLastError();
 }
 
+template <int D, bool FILTER, bool PAGED>
+hipError_t launch_score_mfma_p(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
+  if (gb <= 4)
+    hipLaunchKernelGGL((score_mfma_kernel<D, 4, FILTER, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
+  else if (gb <= 8)
+    hipLaunchKernelGGL((score_mfma_kernel<D, 8, FILTER, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
+  else
+    hipLaunchKernelGGL((score_mfma_kernel<D, 16, FILTER, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
+  return hipGetLastError();
+}
+
 template <int D, bool FILTER>
 hipError_t launch_score_mfma(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
-  if (gb <= 4)
-    hipLaunchKernelGGL((score_mfma_kernel<D, 4, FILTER>), grid, dim3(kScoreThreads), 0, s, p, gb);
-  else if (gb <= 8)
-    hipLaunchKernelGGL((score_mfma_kernel<D, 8, FILTER>), grid, dim3(kScoreThreads), 0, s, p, gb);
-  else
-    hipLaunchKernelGGL((score_mfma_kernel<D, 16, FILTER>), grid, dim3(kScoreThreads), 0, s, p, gb);
-  return hipGetLastError();
+  return p.pm.table ? launch_score_mfma_p<D, FILTER, true>(p, gb, grid, s)
+                    : launch_score_mfma_p<D, FILTER, false>(p, gb, grid, s);
 }
 
 }  // namespace

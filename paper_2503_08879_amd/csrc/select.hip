@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
   for (int64_t i = tid; i < E; i += kTopkThreads) {
     const float v = cand[i];
-    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, S + i,
+    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, S + i,
                                  g_lo, g_hi);
   }
   __syncthreads();
@@ -111,8 +111,6 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int sub = threadIdx.x / LPT, cl = threadIdx.x % LPT;
   constexpr int TPI = kGatherThreads / LPT;  // tokens per iteration
-  const char* Kr = (const char*)p.K + ((int64_t)prob * p.ks_problem + (int64_t)c * p.ks_head) * eb;
-  const char* Vr = (const char*)p.V + ((int64_t)prob * p.vs_problem + (int64_t)c * p.vs_head) * eb;
   const int64_t row_bytes = (int64_t)p.geo.D * eb;
   char* Kc = (char*)p.Kc + (int64_t)row * p.cap * row_bytes;
   char* Vc = (char*)p.Vc + (int64_t)row * p.cap * row_bytes;
@@ -124,8 +122,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
     if (t < p.n_kept) {
       int64_t src = kept[t];
       src = src < 0 ? 0 : (src >= p.geo.L ? p.geo.L - 1 : src);  // never read outside the row
-      const uint4 a = ld16(Kr + src * p.ks_token * eb + cl * 16);
-      const uint4 b = ld16(Vr + src * p.vs_token * eb + cl * 16);
+      const int64_t ko = kv_offset(p.pm, p.pm.ks_page, p.ks_problem, p.ks_head, p.ks_token, prob, c, src);
+      const int64_t vo = kv_offset(p.pm, p.pm.vs_page, p.vs_problem, p.vs_head, p.vs_token, prob, c, src);
+      const uint4 a = ld16((const char*)p.K + ko * eb + cl * 16);
+      const uint4 b = ld16((const char*)p.V + vo * eb + cl * 16);
       st16(Kc + t * row_bytes + cl * 16, a);
       st16(Vc + t * row_bytes + cl * 16, b);
     }
