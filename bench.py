@@ -114,6 +114,31 @@ def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
     }, kept
 
 
+def select_layer_sequential(sk, torch, cfg, head_mode, Bt, q_last, K, V, Kc, Vc, kept):
+    """The eviction pass in the order a prefill produces the cache: one call per layer (batch x KV
+    heads rows), one after the other on one stream.  In a model each call would overlap the next
+    layer's prefill; here they run back to back.  Reported beside the headline, never as it."""
+    lb = cfg.batch
+    sl0 = slice(0, lb)
+    ldesc = sk.select_desc(q_last[sl0], K[sl0], V[sl0], cfg.n_sink, cfg.n_recent, cfg.k, Bt, head_mode=head_mode)
+    lws = torch.empty(sk.sagekv_select_workspace_bytes(ldesc), dtype=torch.uint8, device="cuda")
+
+    def run():
+        for l in range(cfg.n_layers):
+            sl = slice(l * lb, (l + 1) * lb)
+            sk.sagekv_select(ldesc, q_last[sl], K[sl], V[sl], Kc[sl], Vc[sl], kept[sl], None, lws)
+
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    return {"calls": cfg.n_layers, "ms_all_layers": round(ms, 4), "ms_per_layer": round(ms / cfg.n_layers, 4)}
+
+
 def layer_sequential(sk, torch, cfg, head_mode, Bt, q_steps, kn_steps, vn_steps, Kc, Vc, out, n_steps):
     """Decode in the dependency order of a real model: one call per layer (its batch x KV heads
     rows only), layers one after the other.  Timed eagerly (one library call per layer from
@@ -335,6 +360,9 @@ def main():
                      "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(score_ms, 4),
                      "algorithmic_bytes": score_b, "traffic": read_traffic(cfg.name)},
     }
+    if args.layer_sequential_steps > 0 and pages is None:
+        result["select"]["layer_sequential"] = select_layer_sequential(sk, torch, cfg, head_mode, Bt, q_last, K, V,
+                                                                       Kc, Vc, kept)
     if n_dec and args.layer_sequential_steps > 0:
         result["decode"]["layer_sequential"] = layer_sequential(
             sk, torch, cfg, head_mode, Bt, q_steps, kn_steps, vn_steps, Kc, Vc, out,

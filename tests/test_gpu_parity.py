@@ -225,6 +225,37 @@ def test_select_C2_shape_two_layers(ref):
         assert set(pos[r].tolist()) <= set(kept[r].tolist())
 
 
+def test_layer_by_layer_on_two_streams_equals_one_batched_call():
+    """Per-layer streaming: the pass of layer l is enqueued on a side stream as soon as that layer's
+    cache exists (its own workspace per stream), while the caller goes on; results are those of one
+    call over all layers."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    layers, Hq, Hkv, d, L, S, W, k = 6, 8, 2, 128, 36000, 4, 128, 700
+    q, K, V = rand_case(321, layers, Hq, Hkv, d, L, BF16)
+    whole = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=False)
+    assert whole["redone"] == 0
+    qd, Kd, Vd = (synth.host_to_torch(x, BF16) for x in (q, K, V))
+    Bt = S + k + W
+    Kc = torch.zeros((layers, Hkv, Bt, d), dtype=qd.dtype, device="cuda")
+    Vc = torch.zeros_like(Kc)
+    kept = torch.zeros((layers, Hkv, Bt), dtype=torch.int32, device="cuda")
+    desc = sk.select_desc(qd[:1], Kd[:1], Vd[:1], S, W, k, Bt)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [torch.empty(sk.sagekv_select_workspace_bytes(desc), dtype=torch.uint8, device="cuda") for _ in streams]
+    torch.cuda.synchronize()
+    for l in range(layers):
+        with torch.cuda.stream(streams[l % 2]):
+            sl = slice(l, l + 1)
+            sk.sagekv_select(desc, qd[sl], Kd[sl], Vd[sl], Kc[sl], Vc[sl], kept[sl], None, wss[l % 2])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(kept.cpu().numpy(), whole["kept"])
+    np.testing.assert_array_equal(synth.torch_to_host(Kc, BF16), whole["Kc"])
+    np.testing.assert_array_equal(synth.torch_to_host(Vc, BF16), whole["Vc"])
+
+
 def test_prefiltered_select_is_deterministic():
     """The candidate lists are filled in whatever order the workgroups run; the result must not depend on it."""
     q, K, V = rand_case(14, 2, 8, 2, 128, 40000, BF16)
