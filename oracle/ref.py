@@ -38,7 +38,7 @@ def lib():
     if _lib is None:
         _lib = ctypes.CDLL(build())
         for name in ("sagekv_ref_scores", "sagekv_ref_select", "sagekv_ref_append", "sagekv_ref_decode_attn",
-                     "sagekv_ref_full_attention", "sagekv_ref_threads"):
+                     "sagekv_ref_decode_attn_window_rope", "sagekv_ref_full_attention", "sagekv_ref_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -116,6 +116,23 @@ def decode_attn(dtype, head_mode, q, Kc, Vc, length, S=0, k=0, W=0):
                                       _p(out))
     if rc:
         raise ValueError(f"sagekv_ref_decode_attn: {rc}")
+    return out
+
+
+def decode_attn_window_rope(dtype, q, Kc, Vc, length, inv_freq):
+    """StreamLLM_R decode attention: un-rotated q [P,Hq,d] and Kc [P,Hkv,cap,d] (window order), rotary
+    positions = window indices, query at length-1; inv_freq fp64 [d/2] -> out fp32 [P,Hq,d]."""
+    for a in (q, Kc, Vc):
+        _check(a, dtype)
+    P, Hq, d = q.shape
+    _, Hkv, cap, _ = Kc.shape
+    f = np.ascontiguousarray(inv_freq, dtype=np.float64)
+    assert f.shape == (d // 2,)
+    out = np.empty((P, Hq, d), dtype=np.float32)
+    rc = lib().sagekv_ref_decode_attn_window_rope(dtype, P, Hq, Hkv, d, cap, length, _p(q), _p(Kc), _p(Vc), _p(f),
+                                                  _p(out))
+    if rc:
+        raise ValueError(f"sagekv_ref_decode_attn_window_rope: {rc}")
     return out
 
 

@@ -282,6 +282,68 @@ int sagekv_ref_decode_attn(int dtype, int head_mode, int P, int Hq, int Hkv, int
   return err;
 }
 
+/* StreamLLM_R decode attention (Sec. 3.1 baselines (3a); App. A.1): the cache holds keys WITHOUT
+ * rotary embedding and positions are those inside the window, not those of the original
+ * sequence: the cache entry at window index i gets position i, the query (the newest entry, at
+ * index len-1) gets position len-1, so positions stay in [0, len) however long the text grows.
+ *   Rotary embedding at position p (RoFormer), pairs (j, j + d/2), angle p * inv_freq[j]:
+ *     x'[j]       = x[j] cos - x[j + d/2] sin
+ *     x'[j + d/2] = x[j + d/2] cos + x[j] sin
+ *   q [P,Hq,d] and Kc [P,Hkv,cap,d] un-rotated, Kc/Vc rows in window order (sink first, then the
+ *   recent tokens oldest to newest); inv_freq [d/2] fp64; out [P,Hq,d] fp32.
+ * Everything in fp64 on the stored element values; one rounding to fp32 at the end.  The paper
+ * does not print the pairing or the frequencies: the pairing is that of the Hugging Face
+ * Llama/Qwen code the paper integrates with, the frequencies are an input.              */
+int sagekv_ref_decode_attn_window_rope(int dtype, int P, int Hq, int Hkv, int d, int cap, int len, const void* q,
+                                       const void* Kc, const void* Vc, const double* inv_freq, float* out) {
+  if (P < 1 || Hkv < 1 || Hq % Hkv || d < 2 || d % 2 || len < 1 || len > cap) return 1;
+  int G = Hq / Hkv, half = d / 2;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic)
+  for (int ph = 0; ph < P * Hq; ++ph) {
+    int p = ph / Hq, h = ph % Hq, c = h / G;
+    int64_t kv_off = ((int64_t)p * Hkv + c) * cap * d;
+    double* qr = (double*)malloc(sizeof(double) * d);
+    double* w = (double*)malloc(sizeof(double) * len);
+    if (!qr || !w) {
+      err = 2;
+    } else {
+      double pq = (double)(len - 1);
+      for (int j = 0; j < half; ++j) {
+        double a = load_elem(q, dtype, (int64_t)ph * d + j), b = load_elem(q, dtype, (int64_t)ph * d + j + half);
+        double cs = cos(pq * inv_freq[j]), sn = sin(pq * inv_freq[j]);
+        qr[j] = a * cs - b * sn;
+        qr[j + half] = b * cs + a * sn;
+      }
+      double best = -INFINITY;
+      for (int i = 0; i < len; ++i) {
+        double dot = 0.0;
+        for (int j = 0; j < half; ++j) {
+          double a = load_elem(Kc, dtype, kv_off + (int64_t)i * d + j);
+          double b = load_elem(Kc, dtype, kv_off + (int64_t)i * d + j + half);
+          double cs = cos((double)i * inv_freq[j]), sn = sin((double)i * inv_freq[j]);
+          dot += qr[j] * (a * cs - b * sn) + qr[j + half] * (b * cs + a * sn);
+        }
+        w[i] = dot / sqrt((double)d);
+        if (w[i] > best) best = w[i];
+      }
+      double denom = 0.0;
+      for (int i = 0; i < len; ++i) {
+        w[i] = exp(w[i] - best);
+        denom += w[i];
+      }
+      for (int j = 0; j < d; ++j) {
+        double num = 0.0;
+        for (int i = 0; i < len; ++i) num += w[i] * load_elem(Vc, dtype, kv_off + (int64_t)i * d + j);
+        out[(int64_t)ph * d + j] = (float)(num / denom);
+      }
+    }
+    free(qr);
+    free(w);
+  }
+  return err;
+}
+
 /* Independent plain attention of G query heads over one KV row, used to check the
  * "nothing evicted equals full attention" invariant.  Deliberately a different code
  * path from attend(): three explicit passes, positions given by an optional list.

@@ -325,6 +325,57 @@ def test_per_query_decode_uses_own_list(ref):
 
 
 # ------------------------------------------------------------------ paper's printed values
+# ------------------------------------------------------------------ StreamLLM_R (window-relative rotary positions)
+def inv_freq_of(d, base=500000.0):
+    return base ** (-np.arange(0, d, 2, dtype=np.float64) / d)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_window_rope_equals_the_complex_form_of_rotary_attention(ref, dtype):
+    """RoFormer's complex form: with z_j = x[j] + i x[j + d/2], the rotated dot product is
+    Re sum_j zq_j conj(zk_j) exp(i theta_j (p_q - p_k)): the logits depend on position DIFFERENCES
+    only.  Written with library complex arithmetic, no rotation of either vector."""
+    P, Hq, Hkv, d, n = 2, 6, 2, 16, 29
+    q, Kc, Vc = rand_inputs(31, P, Hq, Hkv, d, n + 2, dtype)
+    f = inv_freq_of(d, 100.0)  # a small base: angles up to ~28 rad, every pair turns visibly
+    out = ref.decode_attn_window_rope(dtype, q, Kc, Vc, n, f)
+    q64, K64, V64 = (synth.to_f64(x, dtype) for x in (q, Kc, Vc))
+    h = d // 2
+    zq = q64[..., :h] + 1j * q64[..., h:]
+    zk = K64[..., :n, :h] + 1j * K64[..., :n, h:]
+    delta = (n - 1) - np.arange(n)                      # p_q - p_k
+    turn = np.exp(1j * delta[:, None] * f[None, :])     # [n, h]
+    G = Hq // Hkv
+    want = np.empty((P, Hq, d))
+    for p in range(P):
+        for hq in range(Hq):
+            logit = np.real((zq[p, hq][None, :] * np.conj(zk[p, hq // G]) * turn).sum(-1)) / math.sqrt(d)
+            w = np.exp(logit - logit.max())
+            want[p, hq] = (w / w.sum()) @ V64[p, hq // G, :n]
+    np.testing.assert_allclose(out, want.astype(np.float32), rtol=2e-6, atol=1e-7)
+
+
+def test_window_rope_special_cases(ref):
+    P, Hq, Hkv, d, n = 1, 4, 2, 8, 12
+    q, Kc, Vc = rand_inputs(32, P, Hq, Hkv, d, n, F32)
+    # zero frequencies: no rotation at all, plain attention
+    plain = ref.decode_attn(F32, GROUP_SUM, q, Kc, Vc, n)
+    np.testing.assert_array_equal(ref.decode_attn_window_rope(F32, q, Kc, Vc, n, np.zeros(d // 2)), plain)
+    # one entry: query and key share position 0, the output is that value row
+    out1 = ref.decode_attn_window_rope(F32, q, Kc, Vc, 1, inv_freq_of(d))
+    for h in range(Hq):
+        np.testing.assert_array_equal(out1[0, h], Vc[0, h // 2, 0])
+    # d = 2, theta = pi/2, q = k = (s, 0): logit(distance D) = s^2 cos(D pi/2) / sqrt(2)
+    s_ = 3.0
+    q2 = np.array([[[s_, 0.0]]], dtype=np.float32)
+    K2 = np.tile(np.array([s_, 0.0], dtype=np.float32), (1, 1, 4, 1))
+    V2 = np.eye(4, 2, dtype=np.float32).reshape(1, 1, 4, 2) + np.arange(4, dtype=np.float32).reshape(1, 1, 4, 1)
+    out = ref.decode_attn_window_rope(F32, q2, K2, V2, 4, np.array([math.pi / 2]))
+    logit = np.array([s_ * s_ * math.cos((3 - i) * math.pi / 2) for i in range(4)]) / math.sqrt(2.0)
+    w = np.exp(logit - logit.max())
+    np.testing.assert_allclose(out[0, 0], (w / w.sum()) @ V2[0, 0].astype(np.float64), rtol=1e-6)
+
+
 def test_paper_budget_golden(ref):
     path = os.path.join(os.path.dirname(__file__), "golden", "paper_budget.txt")
     rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
