@@ -169,6 +169,26 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* desc, const void* q, 
                                  const void* v_new, void* Kc, void* Vc, int32_t n_appended, float* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Window-relative rotary positions (the StreamLLM_R cache mode of Sec. 3.1, baseline (3a), App. A.1:
+ * the entry at index i of a window of n entries has position i, the query position n-1, so
+ * positions stay bounded however long the generation runs).  Rotary attention depends on position
+ * differences only, so the mode needs no re-rotation of the cache when the window slides: keep the
+ * keys rotated at their ABSOLUTE positions (the usual cache), pass
+ *   q      = the query rotated at its absolute position (recent tokens: the distance to a recent
+ *            token is the same in window and in absolute positions), and
+ *   q_sink = the query rotated at position n-1 = S+k+W-1 (a sink token's absolute position IS its
+ *            window position, so only the query's position differs),
+ * and the sink tokens [0, n_sink) are scored with q_sink, every other token with q.  The rotation
+ * itself belongs to the model around the cache and is not done here.  Everything else is as in
+ * sagekv_decode_attn / sagekv_decode_step; q_sink [n_problems, Hq, head_dim] must not be null. */
+sagekv_status sagekv_decode_attn_window(const sagekv_decode_desc* desc, const void* q, const void* q_sink,
+                                        const void* Kc, const void* Vc, int32_t len, float* out, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream);
+sagekv_status sagekv_decode_step_window(const sagekv_decode_desc* desc, const void* q, const void* q_sink,
+                                        const void* k_new, const void* v_new, void* Kc, void* Vc,
+                                        int32_t n_appended, float* out, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char* sagekv_status_string(sagekv_status s); /* host string, static storage */
 

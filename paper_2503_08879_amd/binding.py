@@ -22,6 +22,7 @@ EXPORTS = (
     "sagekv_select_redone_rows",
     "sagekv_append",
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
+    "sagekv_decode_attn_window", "sagekv_decode_step_window",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read",
 )
 
@@ -90,6 +91,10 @@ def lib():
         L.sagekv_decode_attn.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step.restype = ctypes.c_int
         L.sagekv_decode_step.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.sagekv_decode_attn_window.restype = ctypes.c_int
+        L.sagekv_decode_attn_window.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.sagekv_decode_step_window.restype = ctypes.c_int
+        L.sagekv_decode_step_window.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_stage_timing_enable.restype = ctypes.c_int
         L.sagekv_stage_timing_enable.argtypes = [i32]
         L.sagekv_stage_timing_read.restype = ctypes.c_int
@@ -219,6 +224,19 @@ def sagekv_decode_step(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, n_appended: in
 
 
 # ---------------------------------------------------------------------------------------- timing
+def sagekv_decode_attn_window(desc: DecodeDesc, q, q_sink, Kc, Vc, length: int, out, workspace) -> None:
+    _check(lib().sagekv_decode_attn_window(ctypes.byref(desc), _ptr(q), _ptr(q_sink), _ptr(Kc), _ptr(Vc), length,
+                                           _ptr(out), _ptr(workspace), _ws_bytes(workspace), _stream()),
+           "sagekv_decode_attn_window")
+
+
+def sagekv_decode_step_window(desc: DecodeDesc, q, q_sink, k_new, v_new, Kc, Vc, n_appended: int, out,
+                              workspace) -> None:
+    _check(lib().sagekv_decode_step_window(ctypes.byref(desc), _ptr(q), _ptr(q_sink), _ptr(k_new), _ptr(v_new),
+                                           _ptr(Kc), _ptr(Vc), n_appended, _ptr(out), _ptr(workspace),
+                                           _ws_bytes(workspace), _stream()), "sagekv_decode_step_window")
+
+
 def sagekv_stage_timing_enable(n_calls: int) -> None:
     _check(lib().sagekv_stage_timing_enable(n_calls), "sagekv_stage_timing_enable")
 

@@ -226,7 +226,8 @@ struct StageTimer {
 
 sagekv_status dev(hipError_t e) { return e == hipSuccess ? SAGEKV_OK : SAGEKV_ERR_DEVICE; }
 
-sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void* k_new, const void* v_new,
+sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void* q_sink, const void* k_new,
+                         const void* v_new,
                          void* Kc, void* Vc, int slot, int len, float* out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
   const DecodeLayout l = decode_layout(d);
@@ -239,6 +240,8 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
   p.D = d->head_dim;
   p.dtype = d->dtype;
   p.q = q;
+  p.q_sink = q_sink;
+  p.qs_S = q_sink ? d->n_sink : 0;
   p.Kc = Kc;
   p.Vc = Vc;
   p.k_new = k_new;
@@ -614,8 +617,18 @@ sagekv_status sagekv_decode_attn(const sagekv_decode_desc* d, const void* q, con
   sagekv_status st;
   if (!check_decode(d, &st)) return st;
   if (!q || !Kc || !Vc || !out || len < 1 || len > d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
-  return run_decode(d, q, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, out, workspace,
-                    workspace_bytes, (hipStream_t)hip_stream);
+  return run_decode(d, q, nullptr, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, out,
+                    workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+sagekv_status sagekv_decode_attn_window(const sagekv_decode_desc* d, const void* q, const void* q_sink, const void* Kc,
+                                        const void* Vc, int32_t len, float* out, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_decode(d, &st)) return st;
+  if (!q || !q_sink || !Kc || !Vc || !out || len < 1 || len > d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
+  return run_decode(d, q, q_sink, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, out,
+                    workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
 sagekv_status sagekv_decode_step(const sagekv_decode_desc* d, const void* q, const void* k_new, const void* v_new,
@@ -628,7 +641,21 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* d, const void* q, con
   const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
   const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
-  return run_decode(d, q, k_new, v_new, Kc, Vc, (int)slot, (int)len, out, workspace, workspace_bytes,
+  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, (int)slot, (int)len, out, workspace, workspace_bytes,
+                    (hipStream_t)hip_stream);
+}
+
+sagekv_status sagekv_decode_step_window(const sagekv_decode_desc* d, const void* q, const void* q_sink,
+                                        const void* k_new, const void* v_new, void* Kc, void* Vc, int32_t n_appended,
+                                        float* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_decode(d, &st)) return st;
+  if (!q || !q_sink || !k_new || !v_new || !Kc || !Vc || !out || n_appended < 0) return SAGEKV_ERR_INVALID_ARG;
+  const int base = d->n_sink + decode_lists(d) * d->k;
+  const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
+  const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
+  if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
+  return run_decode(d, q, q_sink, k_new, v_new, Kc, Vc, (int)slot, (int)len, out, workspace, workspace_bytes,
                     (hipStream_t)hip_stream);
 }
 

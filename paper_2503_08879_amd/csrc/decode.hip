@@ -50,11 +50,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
     st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
   }
 
-  uint4 q[GB];
+  uint4 q[GB], q2[GB];  // q2: the sink tokens' query (window-relative positions), else = q
 #pragma unroll
   for (int g = 0; g < GB; ++g) {
     const int h = c * p.G + g0 + g;
     q[g] = ld16((const char*)p.q + (((int64_t)prob * p.Hq + h) * D + cl * EPL) * EB);
+    q2[g] = p.q_sink ? ld16((const char*)p.q_sink + (((int64_t)prob * p.Hq + h) * D + cl * EPL) * EB) : q[g];
   }
   float m[GB], l[GB], acc[GB][EPL];
 #pragma unroll
@@ -83,8 +84,9 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
     for (int i = 0; i < SB; ++i)
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
-        const float v = group_sum<LPT>(dot16<DT>(kv[i], q[g], 0.f)) * p.scale;
-        x[i][g] = valid[i] && head_attends(p.pq_S, p.pq_k, p.G, g0 + g, t0 + i * TPL + tq) ? v : -INFINITY;
+        const int tok = t0 + i * TPL + tq;
+        const float v = group_sum<LPT>(dot16<DT>(kv[i], tok < p.qs_S ? q2[g] : q[g], 0.f)) * p.scale;
+        x[i][g] = valid[i] && head_attends(p.pq_S, p.pq_k, p.G, g0 + g, tok) ? v : -INFINITY;
       }
     float mn[GB];
     bool any = false;
@@ -240,16 +242,17 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   }
   // A operand of tile slot ts, k-step kc, kept in LDS (registers are short here): lane (row m = n,
   // k-group j) reads q[head m % GPAD][8*(4*kc + j) ..+8] if m / GPAD == ts, zeros otherwise
-  __shared__ uint4 qbuf[NT][KSTEPS][64];
-  for (int it = tid; it < NT * KSTEPS * 64; it += kThreads) {
-    const int l = it & 63, kc = (it >> 6) % KSTEPS, ts = it / (64 * KSTEPS);
+  // Set 1 holds the query the sink tokens are scored with, when the caller gives one.
+  __shared__ uint4 qbuf[2][NT][KSTEPS][64];
+  for (int it = tid; it < (p.q_sink ? 2 : 1) * NT * KSTEPS * 64; it += kThreads) {
+    const int l = it & 63, kc = (it >> 6) % KSTEPS, ts = (it / (64 * KSTEPS)) % NT, set = it / (64 * KSTEPS * NT);
     const int m = l & 15, jj = l >> 4;
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
     if (m % GPAD < gb && m / GPAD == ts) {
       const int h = c * p.G + g0 + m % GPAD;
-      v = ld16((const char*)p.q + (((int64_t)prob * p.Hq + h) * D + (4 * kc + jj) * 8) * 2);
+      v = ld16((const char*)(set ? p.q_sink : p.q) + (((int64_t)prob * p.Hq + h) * D + (4 * kc + jj) * 8) * 2);
     }
-    qbuf[ts][kc][l] = v;
+    qbuf[set][ts][kc][l] = v;
   }
   __syncthreads();
   for (int b = wave; b < nblk; b += NW) {
@@ -264,16 +267,22 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
     if (more) load_block(b + NW, kv, Kr, kn);
 
     // logits of the block
-    f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f}, ds = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const bool sink_blk = p.q_sink && t_begin + b * BT < p.qs_S;  // wave-uniform: the block holds sink tokens
 #pragma unroll
     for (int ts = 0; ts < NT; ++ts) {
       const int t = ts * 16 + n;
 #pragma unroll
       for (int kc = 0; kc < KSTEPS; ++kc) {
         const uint4 bb = buf[t * CH + ((4 * kc + j) ^ (n & (CH - 1)))];
-        const uint4 qv = qbuf[ts][kc][lane];
+        const uint4 qv = qbuf[0][ts][kc][lane];
         d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qv), __builtin_bit_cast(bf16x8_t, bb), d,
                                                     0, 0, 0);
+        if (sink_blk) {
+          const uint4 qs = qbuf[1][ts][kc][lane];
+          ds = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qs), __builtin_bit_cast(bf16x8_t, bb),
+                                                       ds, 0, 0, 0);
+        }
       }
     }
     const int tok = t_begin + b * BT + t_mine;
@@ -281,7 +290,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       x[r] = (tile < NT && tok < t_end && hbase + r < gb && head_attends(p.pq_S, p.pq_k, p.G, g0 + hbase + r, tok))
-                 ? d[r] * p.scale
+                 ? (sink_blk && tok < p.qs_S ? ds[r] : d[r]) * p.scale
                  : -INFINITY;
 
     // online softmax, once per (token, head); lanes with the same heads agree on the maximum

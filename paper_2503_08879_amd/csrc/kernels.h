@@ -203,6 +203,8 @@ struct GatherParams {
 struct DecodeParams {
   int n_problems, Hq, Hkv, G, D, dtype;
   const void* q;       // [P][Hq][D]
+  const void* q_sink;  // nullable [P][Hq][D]: the query the sink tokens [0, qs_S) are scored with
+  int qs_S;
   void* Kc;            // [rows][cap][D]
   void* Vc;
   const void* k_new;   // nullable: [rows][D]
