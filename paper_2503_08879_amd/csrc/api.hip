@@ -36,11 +36,6 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
          !(d->flags & SAGEKV_SELECT_DENSE);
   if (!f.ok) return f;
   const int lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? G : 1;
-  f.cap = (int)(2.5 * d->k) * lists + 4096;  // per-query lists share one candidate list per row
-  if ((int64_t)f.cap * 2 > E) {  // k is a large share of the row: the filter would keep most of it
-    f.ok = false;
-    return f;
-  }
   // sample: runs of 16 consecutive tokens, about 1/64 of the candidates (64 to 512 runs); the
   // sample is read from HBM on top of the full pass over K, so its share is kept small
   int64_t nb = E / 4096;
@@ -60,6 +55,17 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   const double r0 = 1.15 * (double)d->k * (double)(64 * f.nB) / (double)E;
   const double x = 2.0 + sqrt(4.0 + r0);
   f.rank = (int)ceil(x * x);
+  // Room for the candidates: about rank * wB tokens pass a list's threshold, 4 sigma high side
+  // (rank + 4 sqrt(rank)) * wB; per-query lists share one candidate list per row (their union).
+  const double high = ((double)f.rank + 4.0 * sqrt((double)f.rank)) * (double)f.wB;
+  const double planned = 2.5 * (double)d->k;
+  int64_t cap = (int64_t)ceil(high > planned ? high : planned) * lists + 4096;
+  f.cap = (int)(cap < E ? cap : E);
+  // k is a large share of the row: the filter would be expected to keep half of it or more
+  if (2.0 * lists * (double)f.rank * (double)f.wB > (double)E || 5 * (int64_t)d->k * lists > E) {
+    f.ok = false;
+    return f;
+  }
   f.Gs = (G + 3) / 4 * 4;
   return f;
 }
@@ -118,7 +124,6 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
   };
   const size_t rows = (size_t)l.rows;
   l.logits = take(rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
-  l.scores = take(own_scores ? rows * l.n_lists * l.Lp * sizeof(float) : 0);
   l.partials = take(rows * l.G * l.n_chunks * sizeof(float2));
   l.stats = take(rows * l.G * sizeof(RowStat));
   l.ghist = take(rows * l.n_lists * kHistBins * sizeof(int));
@@ -140,6 +145,8 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
     l.fail_list = take(rows * sizeof(int));
     l.n_fail = take(sizeof(int));
   }
+  // last, so that no other offset depends on whether the caller brought its own score rows
+  l.scores = take(own_scores ? rows * l.n_lists * l.Lp * sizeof(float) : 0);
   l.total = off;
   return l;
 }
@@ -453,6 +460,9 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     gate.n_active = n_fail;
     t.begin(SAGEKV_STAGE_REDO);
   }
+
+  // a dense call on a descriptor the fast path could serve: sagekv_select_redone_rows must say "dense"
+  if (!fast && l.fast.ok && launch_fill_u32(ws + l.n_fail, 1, 0xFFFFFFFFu, s) != hipSuccess) return SAGEKV_ERR_DEVICE;
 
   // ---- dense path: every row, or the rows the fast path flagged
   sp.gate = gate;

@@ -428,8 +428,8 @@ __global__ __launch_bounds__(64) void append_kernel(DecodeParams p, int row_byte
   st16(Vr + tid * 16, ld16((const char*)p.v_new + (int64_t)row * row_bytes + tid * 16));
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* p, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0u;
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
 }
 
 template <int DT, int D>
@@ -512,12 +512,12 @@ hipError_t launch_append(const DecodeParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t s) {
-  const size_t n = bytes / 4;
+// A fill kernel instead of a memset: the calls may be recorded into a HIP graph.
+hipError_t launch_fill_u32(void* ptr, size_t n, uint32_t value, hipStream_t s) {
   if (n == 0) return hipSuccess;
   size_t want = (n + 255) / 256;
   unsigned grid = (unsigned)(want < 4096 ? want : 4096);
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, (uint32_t*)ptr, n);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, s, (uint32_t*)ptr, n, value);
   return hipGetLastError();
 }
 

@@ -234,7 +234,7 @@ hipError_t launch_topk(const TopkParams& p, hipStream_t s);
 hipError_t launch_gather(const GatherParams& p, hipStream_t s);
 hipError_t launch_decode(const DecodeParams& p, hipStream_t s);
 hipError_t launch_append(const DecodeParams& p, hipStream_t s);
-hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t s);
+hipError_t launch_fill_u32(void* ptr, size_t n_words, uint32_t value, hipStream_t s);
 
 // Does query head g (index inside its group of G) attend position tok of a reduced row?
 __host__ __device__ inline bool head_attends(int pq_S, int pq_k, int G, int g, int tok) {
