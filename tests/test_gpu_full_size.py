@@ -109,3 +109,48 @@ def test_C5_full(ref):
     # needles at log-uniform positions crowd the first tokens of every row; a row whose sample is
     # dominated by them cannot be certified and is redone densely (same result, checked above)
     assert full_size_case(ref, cfg, problems=[5], n_decode=2) <= cfg.rows // 10
+
+
+def test_C4_per_query_paper_budget_full(ref):
+    """The appendix's own setting for Qwen2.5-7B (App. A.2): B = 8192 -> sink 2048, 512 per query head
+    (7 lists per KV head), recent 2560, one top-k per query head, on the full C4 cache."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    base = synth.CONFIGS["C4"]
+    S, k, W = ref.paper_budget(8192, base.G)
+    assert (S, k, W) == (2048, 512, 2560)
+    cfg = base.with_(n_sink=S, k=k, n_recent=W)
+    G, P, Hq, Hkv, d, L = cfg.G, cfg.n_problems, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.L
+    Bt = S + G * k + W
+    q_last, K, V, pos = synth.kv_device(cfg)
+    desc = sk.select_desc(q_last, K, V, S, W, k, Bt, head_mode=sk.PER_QUERY)
+    ws = torch.empty(sk.sagekv_select_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    Kc = torch.zeros((P, Hkv, Bt, d), dtype=K.dtype, device="cuda")
+    Vc = torch.zeros_like(Kc)
+    kept = torch.full((P, Hkv, Bt), -1, dtype=torch.int32, device="cuda")
+    sk.sagekv_select(desc, q_last, K, V, Kc, Vc, kept, None, ws)
+    torch.cuda.synchronize()
+    redone = sk.sagekv_select_redone_rows(desc, ws)
+    print(f"C4 per-query B=8192: rows redone by the dense path: {redone} of {cfg.rows}", flush=True)
+    assert redone == 0
+    kept_h = kept.cpu().numpy().reshape(cfg.rows, Bt)
+    assert np.array_equal(kept_h[:, :S], np.tile(np.arange(S), (cfg.rows, 1)))
+    assert np.array_equal(kept_h[:, S + G * k:], np.tile(np.arange(L - W, L), (cfg.rows, 1)))
+    for g in range(G):
+        sel = kept_h[:, S + g * k:S + (g + 1) * k]
+        assert np.all(np.diff(sel, axis=1) > 0) and sel.min() >= S and sel.max() < L - W
+    idx = kept.to(torch.int64).view(cfg.rows, Bt, 1).expand(-1, -1, d)
+    assert torch.equal(torch.gather(K.view(cfg.rows, L, d), 1, idx), Kc.view(cfg.rows, Bt, d))
+    assert torch.equal(torch.gather(V.view(cfg.rows, L, d), 1, idx), Vc.view(cfg.rows, Bt, d))
+    del idx
+    qh = synth.q_last_host(cfg)
+    _, nrows = synth.needles(cfg, qh)
+    for p in (3, 100):
+        Kp, Vp = host_problem(cfg, p, pos, nrows)
+        _, _, kept_r, s_r = ref.select(cfg.dtype, 1, qh[p:p + 1], Kp, Vp, S, W, k, want_scores=True)
+        got = kept_h[p * Hkv:(p + 1) * Hkv]
+        for g in range(G):
+            cut = lambda a: np.concatenate([a[..., :S], a[..., S + g * k:S + (g + 1) * k], a[..., S + G * k:]], axis=-1)
+            gu.check_kept(cut(got), cut(kept_r.reshape(Hkv, Bt)), s_r[0][:, g], S, W, k)
