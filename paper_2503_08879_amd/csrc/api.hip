@@ -181,7 +181,7 @@ struct DecodeLayout {
 int splits_for(int rows, int len) {
   if (rows >= 192) return 1;
   int want = (2048 + rows - 1) / rows;
-  int most = (len + 255) / 256;
+  int most = (len + 127) / 128;
   int n = want < most ? want : most;
   return n < 1 ? 1 : n;
 }

@@ -397,25 +397,41 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
 }
 
 // Merges the splits of a row: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
-__global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
-  const int row = blockIdx.x, tid = threadIdx.x;
+__global__ __launch_bounds__(128) void combine_kernel(DecodeParams p) {
+  const int row = blockIdx.x, g = blockIdx.y, j = threadIdx.x;  // one thread per output element
   const int prob = row / p.Hkv, c = row % p.Hkv;
   const int D = p.D;
-  for (int it = tid; it < p.G * D; it += 256) {
-    const int g = it / D, j = it % D;
-    const float2* ml = p.part_ml + (int64_t)row * p.n_splits * p.G + g;
-    const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g) * D + j;
-    float M = -INFINITY;
-    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, ml[(int64_t)s * p.G].x);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < p.n_splits; ++s) {
-      const float2 v = ml[(int64_t)s * p.G];
-      const float f = (v.x == -INFINITY) ? 0.f : exp_fast(v.x - M);
-      num += a[(int64_t)s * p.G * D] * f;
-      den += v.y * f;
+  if (j >= D) return;
+  const float2* ml = p.part_ml + (int64_t)row * p.n_splits * p.G + g;
+  const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g) * D + j;
+  // one pass, eight splits at a time: their loads are independent and in flight together
+  float M = -INFINITY, num = 0.f, den = 0.f;
+  for (int s0 = 0; s0 < p.n_splits; s0 += 8) {
+    float2 v[8];
+    float av[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + u < p.n_splits ? s0 + u : p.n_splits - 1;
+      v[u] = ml[(int64_t)s * p.G];
+      av[u] = a[(int64_t)s * p.G * D];
+      if (s0 + u >= p.n_splits) v[u].x = -INFINITY;
     }
-    p.out[((int64_t)prob * p.Hq + c * p.G + g) * D + j] = num / den;
+    float Mn = M;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) Mn = fmaxf(Mn, v[u].x);
+    if (Mn == -INFINITY) continue;  // nothing attended in these splits (uniform over the workgroup)
+    const float f0 = (M == -INFINITY) ? 0.f : exp_fast(M - Mn);
+    num *= f0;
+    den *= f0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float f = (v[u].x == -INFINITY) ? 0.f : exp_fast(v[u].x - Mn);
+      num = fmaf(av[u], f, num);
+      den = fmaf(v[u].y, f, den);
+    }
+    M = Mn;
   }
+  p.out[((int64_t)prob * p.Hq + c * p.G + g) * D + j] = num / den;
 }
 
 template <int LPT>
@@ -493,7 +509,7 @@ hipError_t launch_decode(const DecodeParams& p, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   if (p.n_splits > 1) {
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)rows), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)rows, (unsigned)p.G), dim3(128), 0, s, p);
     return hipGetLastError();
   }
   return hipSuccess;
