@@ -396,6 +396,238 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   }
 }
 
+// bf16 decode with BOTH products on the matrix cores.  q.K as in decode_mfma_kernel.  The softmax
+// weights of a 32-token block are rounded to bf16 (as the values are) and written to LDS as
+// P[head][token]; V goes through the wave's staging buffer like K, and a lane assembles the MFMA B
+// operand V[8 tokens][its dim] from 8 dword reads (one per token, two dims each) and 4 byte permutes.
+// out[head][dim] accumulates in one 16x16 tile per 16 dims, rows = heads, so the accumulator does not
+// grow with the group size and the vector ALU no longer does G x head_dim multiply-adds per token.
+__device__ __forceinline__ uint32_t bf16_rne(float f) {  // finite, non-negative input
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+template <int D, int GPAD, int NW, bool STREAM>
+__global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p, int g0, int gb) {
+  constexpr int BT = 32;
+  constexpr int CH = D / 8, TPL = 64 / CH, NLOAD = BT / TPL, KSTEPS = D / 32;
+  constexpr int TILES = 16 / GPAD;                       // 16-token tiles sharing a q.K accumulator
+  constexpr int NT = BT / 16;                            // token tiles per block
+  constexpr int NACC = NT > TILES ? NT / TILES : 1;      // q.K accumulators per block
+  constexpr int NDT = D / 16;                            // output tiles (16 dims each)
+  constexpr int ROWB = D * 2;
+  constexpr int VSW = CH == 16 ? 2 : 1;                  // V staging swizzle: chunk ^= (token / 8) << VSW
+  constexpr int kThreads = NW * 64;
+  static_assert(GPAD * D * 4 <= BT * CH * 16, "accumulators fit the staging buffers");
+
+  __shared__ uint4 kbuf[NW][BT * CH];  // K staging, then V staging, at the end the waves' accumulators
+  __shared__ __attribute__((aligned(16))) unsigned short pT[NW][16][BT];  // weights, bf16, [head][token]
+  __shared__ float2 s_ml[NW][GPAD];
+  __shared__ uint4 qbuf[2][NT][KSTEPS][64];
+
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int prob = row / p.Hkv, c = row % p.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tq = lane / CH, cl = lane % CH;  // load role: token sub-index, 16-byte chunk
+  const int n = lane & 15, j = lane >> 4;    // MFMA role: column, row block / k-group
+
+  char* Kr = (char*)p.Kc + (int64_t)row * p.cap * ROWB;
+  char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
+  const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
+  const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
+  const int slot = kn ? p.slot : -1;
+  const int t_begin = split * p.tokens_per_split;
+  const int t_end = min(p.len, t_begin + p.tokens_per_split);
+  if (slot >= t_begin && slot < t_end && tid < CH) {  // Step 4: the new token enters the window
+    st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
+    st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
+  }
+
+  // q.K accumulator a, register r of lane (j, n): head hbase + r, token tile a * TILES + tslot, column n
+  const int hbase = (4 * j) % GPAD, tslot = (4 * j) / GPAD;
+  float m_run[4], l_part[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    m_run[r] = -INFINITY;
+    l_part[r] = 0.f;
+  }
+  f32x4_t acc[NDT];  // out[head 4j + r][dim 16 * nd + n]
+#pragma unroll
+  for (int nd = 0; nd < NDT; ++nd) acc[nd] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  uint4* buf = kbuf[wave];
+  uint32_t* buf32 = reinterpret_cast<uint32_t*>(buf);
+  reinterpret_cast<uint4*>(&pT[wave][0][0])[lane] = make_uint4(0u, 0u, 0u, 0u);  // rows of absent heads stay 0
+  const int nblk = (t_end - t_begin + BT - 1) / BT;
+  uint4 kv[NLOAD], vv[NLOAD];
+  auto load_block = [&](int b, uint4* dst, const char* base, const char* fresh) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int tok = t_begin + b * BT + i * TPL + tq;
+      const int tc = tok < t_end ? tok : t_begin;
+      const char* src = (tc == slot) ? fresh : base + (int64_t)tc * ROWB;
+      dst[i] = STREAM ? ld16_stream(src + cl * 16) : ld16(src + cl * 16);
+    }
+  };
+  if (wave < nblk) {
+    load_block(wave, kv, Kr, kn);
+    load_block(wave, vv, Vr, vn);
+  }
+  for (int it = tid; it < (p.q_sink ? 2 : 1) * NT * KSTEPS * 64; it += kThreads) {
+    const int l = it & 63, kc = (it >> 6) % KSTEPS, ts = (it / (64 * KSTEPS)) % NT, set = it / (64 * KSTEPS * NT);
+    const int m = l & 15, jj = l >> 4;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (m % GPAD < gb && m / GPAD == ts % TILES) {
+      const int h = c * p.G + g0 + m % GPAD;
+      v = ld16((const char*)(set ? p.q_sink : p.q) + (((int64_t)prob * p.Hq + h) * D + (4 * kc + jj) * 8) * 2);
+    }
+    qbuf[set][ts][kc][l] = v;
+  }
+  __syncthreads();
+
+  // this lane's part of the V operand: dims 16 * nd + n, tokens 8j .. 8j+7 of the block (token / 8 = j)
+  const uint32_t v_sel = (n & 1) ? 0x07060302u : 0x05040100u;  // high or low halves of two dwords
+  const int v_lane = (8 * j) * CH * 4 + ((n & 7) >> 1);      // dword index of token 8j, chunk 0
+
+  for (int b = wave; b < nblk; b += NW) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // last block's reads of the buffer are done
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int t = i * TPL + tq;
+      buf[t * CH + (cl ^ (t & (CH - 1)))] = kv[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    const bool more = b + NW < nblk;
+    if (more) load_block(b + NW, kv, Kr, kn);
+
+    f32x4_t d[NACC], ds[NACC];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) d[a] = ds[a] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const bool sink_blk = p.q_sink && t_begin + b * BT < p.qs_S;  // wave-uniform: the block holds sink tokens
+#pragma unroll
+    for (int ts = 0; ts < NT; ++ts) {
+      const int t = ts * 16 + n, a = ts / TILES;
+#pragma unroll
+      for (int kc = 0; kc < KSTEPS; ++kc) {
+        const uint4 bb = buf[t * CH + ((4 * kc + j) ^ (n & (CH - 1)))];
+        d[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qbuf[0][ts][kc][lane]),
+                                                       __builtin_bit_cast(bf16x8_t, bb), d[a], 0, 0, 0);
+        if (sink_blk)
+          ds[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qbuf[1][ts][kc][lane]),
+                                                          __builtin_bit_cast(bf16x8_t, bb), ds[a], 0, 0, 0);
+      }
+    }
+    float x[NACC][4];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) {
+      const int tile = a * TILES + tslot;
+      const int tok = t_begin + b * BT + tile * 16 + n;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        x[a][r] = (tile < NT && tok < t_end && hbase + r < gb && head_attends(p.pq_S, p.pq_k, p.G, g0 + hbase + r, tok))
+                      ? (sink_blk && tok < p.qs_S ? ds[a][r] : d[a][r]) * p.scale
+                      : -INFINITY;
+    }
+    // online softmax, once per (token, head); lanes with the same heads agree on the maximum
+    float corr[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float bm = x[0][r];
+#pragma unroll
+      for (int a = 1; a < NACC; ++a) bm = fmaxf(bm, x[a][r]);
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) bm = fmaxf(bm, __shfl_xor(bm, o));
+#pragma unroll
+      for (int o = 16 * (GPAD / 4); o < 64; o <<= 1) bm = fmaxf(bm, __shfl_xor(bm, o));
+      const float mn = fmaxf(m_run[r], bm);
+      corr[r] = (mn == -INFINITY) ? 1.f : exp_fast(m_run[r] - mn);
+      float lsum = 0.f;
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) {
+        const uint32_t pb = (x[a][r] == -INFINITY) ? 0u : bf16_rne(exp_fast(x[a][r] - mn));
+        lsum += __uint_as_float(pb << 16);  // the denominator sums the weights the numerator uses
+        const int tile = a * TILES + tslot;
+        if (tile < NT) pT[wave][hbase + r][tile * 16 + n] = (unsigned short)pb;
+      }
+      l_part[r] = l_part[r] * corr[r] + lsum;
+      m_run[r] = mn;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // weights visible; q.K reads of the buffer done
+
+    // V of the block into the staging buffer, V of the next block into the registers
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int t = i * TPL + tq;
+      buf[t * CH + (cl ^ (((t >> 3) & 3) << VSW))] = vv[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if (more) load_block(b + NW, vv, Vr, vn);
+
+    // out += P.V: A = weights [head n][tokens 8j..8j+7], B = values [tokens 8j..8j+7][dim 16 nd + n]
+    const uint4 pa = *reinterpret_cast<const uint4*>(&pT[wave][n][8 * j]);
+#pragma unroll
+    for (int nd = 0; nd < NDT; ++nd) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[nd][r] *= corr[r];  // rows 4j + r are heads hbase + r for every j in use
+      const int chunk = (2 * nd + (n >> 3)) ^ (j << VSW);
+      uint32_t w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) w[u] = buf32[v_lane + u * CH * 4 + chunk * 4];
+      uint4 vb;
+      vb.x = __builtin_amdgcn_perm(w[1], w[0], v_sel);
+      vb.y = __builtin_amdgcn_perm(w[3], w[2], v_sel);
+      vb.z = __builtin_amdgcn_perm(w[5], w[4], v_sel);
+      vb.w = __builtin_amdgcn_perm(w[7], w[6], v_sel);
+      acc[nd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pa), __builtin_bit_cast(bf16x8_t, vb),
+                                                        acc[nd], 0, 0, 0);
+    }
+  }
+
+  // wave totals: sum of weights per head over the lanes that share it
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float ls = l_part[r];
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) ls += __shfl_xor(ls, o);
+#pragma unroll
+    for (int o = 16 * (GPAD / 4); o < 64; o <<= 1) ls += __shfl_xor(ls, o);
+    if (n == 0 && j < GPAD / 4) s_ml[wave][hbase + r] = make_float2(m_run[r], ls);
+  }
+  __syncthreads();  // every wave is done with its staging buffer: reuse it for the accumulators
+  float* s_acc = reinterpret_cast<float*>(&kbuf[0][0]);  // [NW][GPAD][D]
+#pragma unroll
+  for (int nd = 0; nd < NDT; ++nd)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * j + r < GPAD) s_acc[((wave * GPAD) + 4 * j + r) * D + nd * 16 + n] = acc[nd][r];
+  __syncthreads();
+
+  const bool single = p.n_splits == 1;
+  float* pa_out = p.part_acc + (((int64_t)row * p.n_splits + split) * p.G + g0) * D;
+  float2* pml = p.part_ml + ((int64_t)row * p.n_splits + split) * p.G + g0;
+  for (int it = tid; it < gb * D; it += kThreads) {
+    const int g = it / D, jj = it % D;
+    float M = s_ml[0][g].x;
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, s_ml[w][g].x);
+    float a = 0.f, ls = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float2 ml = s_ml[w][g];
+      const float f = (ml.x == -INFINITY) ? 0.f : exp_fast(ml.x - M);
+      a += s_acc[((w * GPAD) + g) * D + jj] * f;
+      ls += ml.y * f;
+    }
+    if (single) {
+      p.out[((int64_t)prob * p.Hq + c * p.G + g0 + g) * D + jj] = a / ls;
+    } else {
+      pa_out[(int64_t)g * D + jj] = a;
+      if (jj == 0) pml[g] = make_float2(M, ls);
+    }
+  }
+}
+
 // Merges the splits of a row: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
 __global__ __launch_bounds__(128) void combine_kernel(DecodeParams p) {
   const int row = blockIdx.x, g = blockIdx.y, j = threadIdx.x;  // one thread per output element
@@ -472,16 +704,22 @@ hipError_t launch_decode_g(const DecodeParams& p, int g0, int gb, dim3 grid, hip
 
 template <int D, bool STREAM>
 hipError_t launch_decode_mfma_s(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
-  // Workgroup size.  A row split over several workgroups: 4 waves.  One workgroup per row: 8 waves, one
-  // workgroup per CU (for 256 < rows <= 512, 4-wave workgroups that are all resident at once were
-  // measured no faster than two rounds of 8-wave ones).
+  // One workgroup per row (many rows): 8 waves, one workgroup per CU; a row split over several
+  // workgroups: 4 waves.  (For 256 < rows <= 512, 4-wave workgroups that are all resident at once
+  // were measured no faster than two rounds of 8-wave ones.)
+  // Up to 4 heads with whole rows, P.V on the vector ALU is a little faster (measured 86 vs 89 us
+  // per step at 256 rows x 4096 tokens); with more heads, or short slices, P.V on the matrix cores
+  // wins clearly (448 rows x 1024 tokens x 7 heads: 47 vs 68 us).
   const bool big = p.n_splits == 1;
   if (gb <= 4) {
     if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
-    else hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 4, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+  } else if (gb <= 8) {
+    if (big) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   } else {
-    if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
-    else hipLaunchKernelGGL((decode_mfma_kernel<D, 8, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+    if (big) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   }
   return hipGetLastError();
 }
@@ -497,8 +735,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, int g0, int gb, dim3 grid, 
 hipError_t launch_decode(const DecodeParams& p, hipStream_t s) {
   const int rows = p.n_problems * p.Hkv;
   dim3 grid((unsigned)p.n_splits, (unsigned)rows);
-  for (int g0 = 0; g0 < p.G; g0 += max_group_per_launch()) {
-    const int gb = p.G - g0 < max_group_per_launch() ? p.G - g0 : max_group_per_launch();
+  const int per_launch = p.dtype == DT_BF16 ? 16 : max_group_per_launch();  // heads one launch handles
+  for (int g0 = 0; g0 < p.G; g0 += per_launch) {
+    const int gb = p.G - g0 < per_launch ? p.G - g0 : per_launch;
     DecodeParams q = p;
     if (g0 > 0) q.k_new = nullptr;  // the first launch already stored the new token
     hipError_t e;

@@ -375,11 +375,30 @@ def decode_case(ref, dtype, P, Hq, Hkv, d, S, k, W, steps, seed, grow=False, fus
         (BF16, 7, 1, 128, 4, 500, 64, 5),    # G=7
         (BF16, 4, 4, 64, 0, 90, 5, 7),       # G=1, d=64, no sink
         (F32, 6, 2, 128, 2, 100, 9, 12),     # fp32 d=128
-        (BF16, 20, 2, 128, 4, 200, 16, 3),   # G=10: two launches per step
+        (BF16, 20, 2, 128, 4, 200, 16, 3),   # G=10: heads padded to 16
+        (BF16, 16, 1, 128, 4, 200, 16, 3),   # G=16: a full tile of heads
+        (BF16, 40, 2, 64, 4, 200, 16, 3),    # G=20: two launches per step (16 + 4), d=64
     ],
 )
 def test_decode_steps_fused(ref, dtype, Hq, Hkv, d, S, k, W, steps):
     decode_case(ref, dtype, 2, Hq, Hkv, d, S, k, W, steps, seed=20 + Hq)
+
+
+@pytest.mark.parametrize(
+    "Hq,Hkv,d,S,k,W",
+    [
+        (8, 2, 128, 4, 250, 47),     # G=4
+        (14, 2, 128, 4, 250, 47),    # G=7
+        (24, 2, 128, 3, 130, 30),    # G=12
+        (16, 1, 64, 4, 250, 47),     # G=16, d=64
+        (3, 3, 64, 0, 100, 33),      # G=1
+    ],
+)
+def test_decode_one_workgroup_per_row(ref, Hq, Hkv, d, S, k, W):
+    """200 rows or more: every row is one workgroup's, no merge launch (the layout of a whole
+    model's decode step)."""
+    P = -(-200 // Hkv)
+    decode_case(ref, BF16, P, Hq, Hkv, d, S, k, W, 3, seed=60 + Hq)
 
 
 def test_decode_steps_separate_append(ref):
