@@ -711,14 +711,17 @@ hipError_t launch_decode_mfma_s(const DecodeParams& p, int g0, int gb, dim3 grid
   // per step at 256 rows x 4096 tokens); with more heads, or short slices, P.V on the matrix cores
   // wins clearly (448 rows x 1024 tokens x 7 heads: 47 vs 68 us).
   const bool big = p.n_splits == 1;
+  // more rows than CUs: 4-wave workgroups, two resident per CU, beat two rounds of 8-wave ones
+  // (measured 43 vs 47 us at 448 rows x 1024 tokens x 7 heads)
+  const bool wide = big && grid.y <= 256;
   if (gb <= 4) {
     if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
     else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 4, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   } else if (gb <= 8) {
-    if (big) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    if (wide) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
     else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   } else {
-    if (big) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
+    if (wide) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
     else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
   }
   return hipGetLastError();

@@ -385,19 +385,21 @@ def test_decode_steps_fused(ref, dtype, Hq, Hkv, d, S, k, W, steps):
 
 
 @pytest.mark.parametrize(
-    "Hq,Hkv,d,S,k,W",
+    "rows,Hq,Hkv,d,S,k,W",
     [
-        (8, 2, 128, 4, 250, 47),     # G=4
-        (14, 2, 128, 4, 250, 47),    # G=7
-        (24, 2, 128, 3, 130, 30),    # G=12
-        (16, 1, 64, 4, 250, 47),     # G=16, d=64
-        (3, 3, 64, 0, 100, 33),      # G=1
+        (200, 8, 2, 128, 4, 250, 47),     # G=4
+        (200, 14, 2, 128, 4, 250, 47),    # G=7
+        (200, 24, 2, 128, 3, 130, 30),    # G=12
+        (200, 16, 1, 64, 4, 250, 47),     # G=16, d=64
+        (200, 3, 3, 64, 0, 100, 33),      # G=1
+        (300, 14, 2, 128, 4, 250, 47),    # more rows than CUs, G=7: 4-wave workgroups
+        (300, 8, 2, 128, 4, 250, 47),     # more rows than CUs, G=4
     ],
 )
-def test_decode_one_workgroup_per_row(ref, Hq, Hkv, d, S, k, W):
-    """200 rows or more: every row is one workgroup's, no merge launch (the layout of a whole
+def test_decode_one_workgroup_per_row(ref, rows, Hq, Hkv, d, S, k, W):
+    """192 rows or more: every row is one workgroup's, no merge launch (the layout of a whole
     model's decode step)."""
-    P = -(-200 // Hkv)
+    P = -(-rows // Hkv)
     decode_case(ref, BF16, P, Hq, Hkv, d, S, k, W, 3, seed=60 + Hq)
 
 
