@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
   __shared__ int band_j[kMaxBand], band_tok[kMaxBand];
   __shared__ float band_v[kMaxBand];
-  __shared__ int n_band, n_above;
+  __shared__ int n_band, n_above, n_list;
   extern __shared__ uint32_t bitmap[];  // one bit per eviction candidate of the row
 
   const int list = blockIdx.x, tid = threadIdx.x;  // one list per row, or one per (row, query head)
@@ -154,18 +154,23 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
     sM[tid] = st.M;
     sInv[tid] = st.invZ;
   }
-  if (tid == 0) n_band = n_above = 0;
+  if (tid == 0) n_band = n_above = n_list = 0;
   __syncthreads();
-  const int n_c = chunk_off[p.n_chunks];
-  if (n_c > p.cap || n_c < k) {  // far more candidates than planned, or the threshold was too high
+  const int n_all = chunk_off[p.n_chunks];
+  if (n_all > p.cap || n_all < k) {  // far more candidates than planned, or the threshold was too high
     if (tid == 0) p.row_fail[row] = 1;
     return;
   }
 
-  // exact fp32 scores of the candidates (same arithmetic and order as the dense combine stage)
+  // Exact fp32 scores of the candidates (same arithmetic and order as the dense combine stage).
+  // The list keeps those that reach the bound: a candidate below it is in the same position as a
+  // token the filter dropped (the row is only accepted if the k-th score's band lies above the
+  // bound), and with per-query lists most of the row's shared candidates came in through other heads.
+  const float bound = p.bound[list];
+  const bool compact = p.n_lists > 1;
   float* cs = p.cand_score + (int64_t)list * p.cap;
   int32_t* ci = p.cand_pos + (int64_t)list * p.cap;
-  for (int d0 = 0; d0 < n_c; d0 += 4 * kTopkThreads) {
+  for (int d0 = 0; d0 < n_all; d0 += 4 * kTopkThreads) {
     int64_t slot[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {  // independent lookups: their loads overlap
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
         const int mid = (lo_c + hi_c) >> 1;
         if (chunk_off[mid] <= dj) lo_c = mid; else hi_c = mid;
       }
-      slot[u] = dj < n_c ? ((int64_t)row * p.n_chunks + lo_c) * kScoreChunk + (dj - chunk_off[lo_c]) : -1;
+      slot[u] = dj < n_all ? ((int64_t)row * p.n_chunks + lo_c) * kScoreChunk + (dj - chunk_off[lo_c]) : -1;
     }
     float4 lg[4][kFastMaxG / 4];
     int32_t ti[4];
@@ -190,8 +195,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int dj = d0 + u * kTopkThreads + tid;
-      if (dj < n_c) {
-        float a = 0.f;
+      float a = 0.f;
+      if (dj < n_all) {
 #pragma unroll
         for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
           if (g4 * 4 < G) {
@@ -200,12 +205,34 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
             for (int e = 0; e < 4; ++e)
               if (g4 * 4 + e >= g_lo && g4 * 4 + e < g_hi) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
           }
-        cs[dj] = a;
-        ci[dj] = ti[u];
+      }
+      if (!compact) {  // one list per row: nearly every candidate reaches the bound, keep them in place
+        if (dj < n_all) {
+          cs[dj] = a;
+          ci[dj] = ti[u];
+        }
+        continue;
+      }
+      const bool keep = dj < n_all && a >= bound;
+      const unsigned long long bal = __ballot(keep);
+      if (bal) {  // wave-uniform
+        int base = 0;
+        if ((tid & 63) == 0) base = atomicAdd(&n_list, __popcll(bal));
+        base = __shfl(base, 0);
+        if (keep) {
+          const int pos = base + __popcll(bal & ((1ull << (tid & 63)) - 1ull));
+          cs[pos] = a;
+          ci[pos] = ti[u];
+        }
       }
     }
   }
   __syncthreads();
+  const int n_c = compact ? n_list : n_all;
+  if (n_c < k) {
+    if (tid == 0) p.row_fail[row] = 1;
+    return;
+  }
 
   // coarse k-th score, then the candidates within the band around it are re-scored in fp64 and
   // ranked exactly (score descending, index ascending); everything above the band is selected
