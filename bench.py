@@ -38,12 +38,13 @@ def algorithmic_bytes(cfg, budget=None):
     return select, decode, score
 
 
-def read_traffic(cfg_name):
-    """HBM bytes per score-kernel launch from the committed rocprofv3 --pmc summary, if present."""
+def read_traffic(cfg_name, key="traffic_bytes_per_launch"):
+    """HBM bytes per launch of the score kernel (or, with another key, of the decode kernel) from the
+    committed rocprofv3 --pmc summary, if present."""
     path = os.path.join(ROOT, "profiles", f"score_kernel_{cfg_name}_pmc.txt")
     if not os.path.exists(path):
         return None
-    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    m = re.search(rf"^{key}:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
     return float(m.group(1)) if m else None
 
 
@@ -356,10 +357,23 @@ def main():
                    "frac_hbm": None if dec_gbps is None else round(dec_gbps / HBM_PEAK_GBPS, 4),
                    "kernel_ms": None if dec_kernel_ms is None else round(dec_kernel_ms, 5),
                    "algorithmic_bytes_per_token": dec_b},
-        "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(score_ms, 4),
-                     "algorithmic_bytes": score_b, "traffic": read_traffic(cfg.name)},
     }
+    # per kernel: algorithmic bytes of one launch / its average duration (HIP events on the launch stream)
+    score_roof = {"kernel": "score_mfma_kernel (the one pass over K of the eviction pass)", "bound": "hbm",
+                  "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                  "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(score_ms, 4),
+                  "algorithmic_bytes": score_b, "traffic": None if pages is not None else read_traffic(cfg.name)}
+    roofs = [score_roof]
+    if n_dec:
+        dec_roof = {"kernel": "decode kernel (one launch = append + attention over all rows)", "bound": "hbm",
+                    "achieved": round(dec_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(dec_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(dec_ms / n_dec, 5),
+                    "algorithmic_bytes": dec_b,
+                    "traffic": read_traffic(cfg.name, "decode_traffic_bytes_per_launch") if lists == 1 else None}
+        roofs.append(dec_roof)
+    # the kernel the step spends most of its time in
+    result["roofline"] = max(roofs, key=lambda r: r["avg_ms"] * (n_dec if r is not score_roof else 1))
+    result["roofline_kernels"] = roofs
     if args.layer_sequential_steps > 0 and pages is None:
         result["select"]["layer_sequential"] = select_layer_sequential(sk, torch, cfg, head_mode, Bt, q_last, K, V,
                                                                        Kc, Vc, kept)
