@@ -533,6 +533,8 @@ def per_query_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps, seed, expect_fa
         (BF16, 1, 7, 1, 128, 5000, 3, 17, 99, 4),      # G=7
         (BF16, 3, 4, 4, 64, 3000, 0, 1, 50, 3),        # G=1: same as group-sum
         (F32, 1, 6, 2, 128, 2000, 5, 33, 0, 3),        # k = 0
+        (BF16, 100, 14, 2, 128, 1500, 8, 32, 40, 2),   # 200 rows, G=7: one workgroup per row in decode
+        (BF16, 150, 8, 2, 128, 1200, 8, 32, 40, 2),    # 300 rows, G=4
     ],
 )
 def test_per_query_mode(ref, dtype, P, Hq, Hkv, d, L, S, W, k, steps):
