@@ -204,6 +204,11 @@ enum { SAGEKV_STAGE_SAMPLE = 0, SAGEKV_STAGE_SCORE = 1, SAGEKV_STAGE_STATS = 2, 
        SAGEKV_STAGE_TOPK = 4, SAGEKV_STAGE_REDO = 5, SAGEKV_STAGE_GATHER = 6, SAGEKV_N_STAGES = 7 };
 sagekv_status sagekv_stage_timing_enable(int32_t n_calls);
 sagekv_status sagekv_stage_timing_read(int32_t which, int32_t call, float* ms /* host */);
+/* Every event record leaves the GPU idle for some microseconds between two kernels (measured ~10 us
+ * on MI355X), so a fully instrumented eviction pass is ~3 % slower than a plain one.  This restricts
+ * the stages of sagekv_select that are bracketed (bit i = stage i; default: all) and says whether
+ * decode calls are (decode != 0; default: yes).  Takes effect for the calls that follow. */
+sagekv_status sagekv_stage_timing_stages(uint32_t select_stage_mask, int32_t decode);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ EXPORTS = (
     "sagekv_append",
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
     "sagekv_decode_attn_window", "sagekv_decode_step_window",
-    "sagekv_stage_timing_enable", "sagekv_stage_timing_read",
+    "sagekv_stage_timing_enable", "sagekv_stage_timing_read", "sagekv_stage_timing_stages",
 )
 
 
@@ -97,6 +97,8 @@ def lib():
         L.sagekv_decode_step_window.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_stage_timing_enable.restype = ctypes.c_int
         L.sagekv_stage_timing_enable.argtypes = [i32]
+        L.sagekv_stage_timing_stages.restype = ctypes.c_int
+        L.sagekv_stage_timing_stages.argtypes = [ctypes.c_uint32, i32]
         L.sagekv_stage_timing_read.restype = ctypes.c_int
         L.sagekv_stage_timing_read.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float)]
         _lib = L
@@ -239,6 +241,12 @@ def sagekv_decode_step_window(desc: DecodeDesc, q, q_sink, k_new, v_new, Kc, Vc,
 
 def sagekv_stage_timing_enable(n_calls: int) -> None:
     _check(lib().sagekv_stage_timing_enable(n_calls), "sagekv_stage_timing_enable")
+
+
+def sagekv_stage_timing_stages(select_stages=None, decode: bool = True) -> None:
+    """Which stages the timed calls bracket with events: a list of names from STAGES (None = all)."""
+    mask = 0xFFFFFFFF if select_stages is None else sum(1 << STAGES.index(n) for n in select_stages)
+    _check(lib().sagekv_stage_timing_stages(mask, int(decode)), "sagekv_stage_timing_stages")
 
 
 def sagekv_stage_timing_read(which: int, call: int):

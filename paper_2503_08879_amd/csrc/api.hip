@@ -207,6 +207,8 @@ struct Timing {
   std::vector<hipEvent_t> sel;  // [n_calls][SAGEKV_N_STAGES][2]
   std::vector<hipEvent_t> dec;  // [n_calls][2]
   std::vector<uint32_t> sel_mask;  // [n_calls] stages that recorded both events
+  uint32_t stages = ~0u;           // select stages to bracket
+  bool decode = true;              // bracket decode calls
 } g_timing;
 
 struct StageTimer {
@@ -220,13 +222,16 @@ struct StageTimer {
       *mask = 0;
       ev = &g_timing.sel[(size_t)g_timing.next_select++ * SAGEKV_N_STAGES * 2];
     }
-    if (which == 1 && g_timing.next_decode < g_timing.n_calls) ev = &g_timing.dec[(size_t)g_timing.next_decode++ * 2];
+    if (which == 1 && g_timing.decode && g_timing.next_decode < g_timing.n_calls)
+      ev = &g_timing.dec[(size_t)g_timing.next_decode++ * 2];
   }
+  bool on(int stage) const { return ev && (!mask || ((g_timing.stages >> stage) & 1u)); }
   void begin(int stage) {
-    if (ev) (void)hipEventRecord(ev[stage * 2], s);
+    if (on(stage)) (void)hipEventRecord(ev[stage * 2], s);
   }
   void end(int stage) {
-    if (ev) (void)hipEventRecord(ev[stage * 2 + 1], s);
+    if (!on(stage)) return;
+    (void)hipEventRecord(ev[stage * 2 + 1], s);
     if (mask) *mask |= 1u << stage;
   }
 };
@@ -686,6 +691,12 @@ sagekv_status sagekv_stage_timing_enable(int32_t n_calls) {
   for (hipEvent_t& e : g_timing.dec)
     if (hipEventCreate(&e) != hipSuccess) return SAGEKV_ERR_DEVICE;
   g_timing.n_calls = n_calls;
+  return SAGEKV_OK;
+}
+
+sagekv_status sagekv_stage_timing_stages(uint32_t select_stage_mask, int32_t decode) {
+  g_timing.stages = select_stage_mask;
+  g_timing.decode = decode != 0;
   return SAGEKV_OK;
 }
 
