@@ -73,7 +73,7 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
 struct SelectLayout {
   size_t logits, scores, partials, stats, ghist, total;
   // fast path
-  size_t samp_logit, samp_score, samp_stats, samp_tau, cand_count, cand_idx, cand_logit, cand_score, cand_pos, bound,
+  size_t samp_logit, samp_stats, samp_tau, cand_count, cand_idx, cand_logit, cand_score, cand_pos, bound,
       row_fail, fail_list, n_fail;
   FastPlan fast;
   int64_t Lp;
@@ -131,7 +131,6 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
     const FastPlan& f = l.fast;
     const size_t ns = (size_t)64 * (f.nA + f.nB + f.nC);
     l.samp_logit = take(rows * ns * f.Gs * sizeof(float));
-    l.samp_score = take(0);
     l.samp_stats = take(rows * l.G * sizeof(float2));
     l.samp_tau = take(rows * l.n_lists * sizeof(float));
     const size_t slots = rows * l.n_chunks * kScoreChunk;  // every token has a slot: chunks cannot overflow

@@ -3,8 +3,8 @@
 // can reach the top-k.
 //
 //   sample_*_kernel   a strided sample of each row -> approximate softmax statistics (M^, Z^) per
-//                     head and a conservative threshold tau^ on the approximate score: the sample
-//                     quantile of rank ~1.5 k/E, so about 1.5 k tokens of the row pass it.
+//                     head and a conservative threshold tau^ on the approximate score: a sample
+//                     quantile chosen so that, four sigma low, 1.15 k tokens of the row still pass.
 //   (score pass)      score_mfma_kernel<FILTER>: exact logits, exact softmax partials; tokens
 //                     whose approximate score reaches tau^ are kept, with their exact fp32 logits,
 //                     in the slots of their score chunk (no global atomics).
@@ -12,9 +12,9 @@
 //                     token that was dropped.
 //   topk_cand_kernel  exact scores of the candidates, radix select of the k-th score, fp64
 //                     re-evaluation and exact ranking of the few candidates around it, then an LDS
-//                     bitmap turns the unordered selection into ascending positions.  The row is only accepted if its k-th score clears the
-//                     bound, i.e. if no dropped token could have been selected; otherwise the row
-//                     is flagged and the dense path redoes it.
+//                     bitmap turns the unordered selection into ascending positions.  The row is
+//                     only accepted if its k-th score clears the bound, i.e. if no dropped token
+//                     could have been selected; otherwise it is flagged and the dense path redoes it.
 #include "device_utils.h"
 #include "kernels.h"
 #include "radix_select.h"

@@ -1,8 +1,11 @@
 // Eviction pass, scoring stage (paper Sec. 2 Step 2: attention scores of the last token's
 // query against the cached keys).
 //
-//   score_kernel    streams K once: logit[g][i] = q[g].K[i]/sqrt(d) for the G heads of a row,
-//                   fp32 logits to scratch, per-chunk softmax partials (max, sum exp).
+//   score_kernel, score_mfma_kernel
+//                   stream K once: logit[g][i] = q[g].K[i]/sqrt(d) for the G heads of a row, per-chunk
+//                   softmax partials (max, sum exp); fp32 logits to scratch (dense path) or only the
+//                   tokens that pass the sample threshold, to the chunk's candidate slots (FILTER).
+//   sample_logits_kernel  logits of the sampled blocks of the pre-filtered path.
 //   stats_kernel    merges the partials of a row into (M, Z) per head, in fp64.
 //   combine_kernel  score[i] = sum_g exp(logit[g][i] - M_g) / Z_g  (fp32) and the first radix
 //                   histogram of the candidates' scores, merged across workgroups with atomics.
