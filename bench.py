@@ -191,6 +191,9 @@ def main():
                          "budget B (sink B/4, k = pow2floor(B/2G) per head, recent = rest) instead of the config's")
     ap.add_argument("--page-size", type=int, default=0, metavar="T",
                     help="hold K and V in shuffled pages of T tokens (block-table layout) and run the paged entry point")
+    ap.add_argument("--q-heads", type=int, default=0, metavar="HQ",
+                    help="override the config's number of query heads (a multiple of its KV heads): other group sizes")
+    ap.add_argument("--dense", action="store_true", help="force the dense eviction path (every token's score is written)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, run one plain 1 GiB device-to-device copy (a reference of "
@@ -213,6 +216,9 @@ def main():
     import synth
 
     cfg = synth.CONFIGS[args.config]
+    if args.q_heads:
+        assert args.q_heads % cfg.n_kv_heads == 0
+        cfg = cfg.with_(n_q_heads=args.q_heads)
     head_mode, lists = sk.GROUP_SUM, 1
     if args.per_query_budget:
         B, G = args.per_query_budget, cfg.G
@@ -259,9 +265,11 @@ def main():
 
     # ---- outputs and workspaces (allocated once, outside the timed region)
     if args.page_size:
-        sdesc, pages = sk.paged_select_desc(q_last, K, V, table, cfg.L, S, W, k, Bt, head_mode=head_mode)
+        sdesc, pages = sk.paged_select_desc(q_last, K, V, table, cfg.L, S, W, k, Bt, head_mode=head_mode,
+                                            flags=sk.SELECT_DENSE if args.dense else 0)
     else:
-        sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt, head_mode=head_mode)
+        sdesc = sk.select_desc(q_last, K, V, S, W, k, Bt, head_mode=head_mode,
+                               flags=sk.SELECT_DENSE if args.dense else 0)
     sws = torch.empty(sk.sagekv_select_workspace_bytes(sdesc), dtype=torch.uint8, device=dev)
     Kc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
     Vc = torch.zeros((P, Hkv, Bt, d), dtype=td, device=dev)
@@ -355,7 +363,8 @@ def main():
             "workload": f"{cfg.name}: {cfg.n_layers} layers x batch {cfg.batch}, {Hq}q/{Hkv}kv heads, head_dim {d}, "
                         f"L={cfg.L}, budget {Bt} = {S} sink + {lists}x{k} top-k + {W} recent, {n_dec} decode steps per step"
                         + (", one top-k per query head" if lists > 1 else "")
-                        + (f", K and V in shuffled pages of {args.page_size} tokens" if args.page_size else ""),
+                        + (f", K and V in shuffled pages of {args.page_size} tokens" if args.page_size else "")
+                        + (", dense eviction path forced" if args.dense else ""),
             "rows": cfg.rows,
             "step": "1 eviction pass over the whole cache + the decode steps",
         },

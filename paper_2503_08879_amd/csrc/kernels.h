@@ -183,7 +183,7 @@ struct TopkCandParams {
   int64_t ks_problem, ks_head, ks_token;
   PageMap pm;
   int32_t* kept_idx;
-  int* row_fail;  // set to 1 when the row must be redone by the general path
+  int* row_fail;  // nonzero (a reason code) when the row must be redone by the general path
   int S, W, k;
   float band;
 };

@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   __syncthreads();
   const int n_c = compact ? n_list : n_all;
   if (n_c < k) {
-    if (tid == 0) p.row_fail[row] = 1;
+    if (tid == 0) p.row_fail[row] = 2;
     return;
   }
 
@@ -244,7 +244,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   // every token outside the list scores below bound[row]: the row is certified only if no such
   // token can reach the band
   if (!(lo * (1.0f - p.band) > p.bound[list])) {
-    if (tid == 0) p.row_fail[row] = 1;
+#ifdef SAGEKV_PROBE_FAILPRINT
+    if (tid == 0) printf("row %d list %d: k-th %g bound %g n_c %d n_all %d k %d\n", row, list, tf, p.bound[list], n_c, n_all, k);
+#endif
+    if (tid == 0) p.row_fail[row] = 3;
     return;
   }
   const int n_words = (int)((E + 31) / 32);
@@ -267,7 +270,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   __syncthreads();
   const int nb = n_band, r = k - n_above;
   if (nb > kMaxBand || r < 1 || r > nb) {  // a degenerate row of (nearly) equal scores: dense path
-    if (tid == 0) p.row_fail[row] = 1;
+    if (tid == 0) p.row_fail[row] = 4;
     return;
   }
   for (int t = tid >> 6; t < nb; t += kTopkWaves) {
@@ -314,6 +317,9 @@ __global__ __launch_bounds__(kTopkThreads) void collect_failed_kernel(const int*
   for (int r0 = 0; r0 < rows; r0 += kTopkThreads) {
     const int r = r0 + threadIdx.x;
     const int f = r < rows ? (row_fail[r] != 0) : 0;
+#ifdef SAGEKV_PROBE_FAILPRINT
+    if (f) printf("row %d fails: reason %d\n", r, row_fail[r]);
+#endif
     int tot;
     const int incl = block_scan_incl<kTopkThreads>(f, wave_tot, &tot);
     if (f) fail_list[run + incl - 1] = r;

@@ -48,9 +48,18 @@ __device__ inline void hist_pass(TopkShared& sh, const float* cand, int64_t E, u
   for (int b = threadIdx.x; b < kHistBins; b += kTopkThreads) sh.hist[b] = 0;
   __syncthreads();
   const uint32_t dm = (1u << nbits) - 1u;
-  for (int64_t i = threadIdx.x; i < E; i += kTopkThreads) {
-    const uint32_t key = __float_as_uint(cand[i]);
-    if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dm], 1);
+  for (int64_t i0 = threadIdx.x; i0 < E; i0 += 4 * kTopkThreads) {  // four independent loads in flight
+    uint32_t key[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + (int64_t)u * kTopkThreads;
+      key[u] = i < E ? __float_as_uint(cand[i]) : ~prefix;  // a key that never matches the prefix
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + (int64_t)u * kTopkThreads;
+      if (i < E && (key[u] & mask) == prefix) atomicAdd(&sh.hist[(key[u] >> shift) & dm], 1);
+    }
   }
   __syncthreads();
 }

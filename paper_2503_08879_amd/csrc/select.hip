@@ -57,10 +57,20 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   // 2. fp64 re-evaluation of the band around it
   const float tf = __uint_as_float(tau);
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
-  for (int64_t i = tid; i < E; i += kTopkThreads) {
-    const float v = cand[i];
-    if (v >= lo && v <= hi) cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row, S + i,
-                                 g_lo, g_hi);
+  for (int64_t i0 = tid; i0 < E; i0 += 4 * kTopkThreads) {  // four independent loads in flight
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + (int64_t)u * kTopkThreads;
+      v[u] = i < E ? cand[i] : -1.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + (int64_t)u * kTopkThreads;
+      if (v[u] >= lo && v[u] <= hi)
+        cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row,
+                                    S + i, g_lo, g_hi);
+    }
   }
   __syncthreads();
 
