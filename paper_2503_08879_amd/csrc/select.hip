@@ -7,11 +7,13 @@
 //      scores (all positive, so the unsigned order is the float order).  The first digit's
 //      histogram was built by many workgroups in the combine stage; the other two are LDS
 //      histograms over the row.
-//   2. every candidate whose fp32 score lies within a relative band of the coarse k-th score is
-//      re-evaluated in fp64 (dot products, exp, fp64-combined normalisers) and its score is
-//      overwritten with the rounded result, so the decision near the threshold does not depend
-//      on fp32 summation order.
-//   3. exact radix select again on the patched scores -> (threshold, number of ties to take).
+//   2. one scan counts the scores above a relative band around the coarse k-th score and lists the
+//      band's members; those are re-evaluated in fp64 (dot products, exp, fp64-combined
+//      normalisers), patched into the score row and ranked exactly among themselves (score
+//      descending, index ascending), so the decision near the threshold does not depend on fp32
+//      summation order.  The exact threshold is the (k - #above)-th of them.
+//   3. only if the band holds more than kDenseBand members (a row of near-ties) or the refined
+//      threshold sits on the band's edge: patch the band, exact radix select of the whole row.
 //   4. ordered compaction: block scans keep the output ascending and give ties to the lowest
 //      indices.
 #include "device_utils.h"
@@ -21,6 +23,8 @@
 namespace sagekv {
 
 namespace {
+
+constexpr int kDenseBand = 1024;  // band members whose exact ranking is done among themselves
 
 template <int DT>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
@@ -54,9 +58,22 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   int quota;
   radix_select(sh, cand, E, k, true, &tau, &quota);
 
-  // 2. fp64 re-evaluation of the band around it
+  // 2. the band around it.  Scores above the band are selected whatever their exact value; the
+  //    members of the band are re-evaluated in fp64 (and patched into the score row).  With a band
+  //    of at most kDenseBand members the exact threshold is found among them alone: it is the
+  //    (k - #above)-th largest refined value, provided it still lies strictly inside the band
+  //    (then no score outside the band can compare differently).  Anything else (a huge band of
+  //    near-ties, a refined value on the band's edge) takes the general route: patch, then a full
+  //    radix select of the patched row.
   const float tf = __uint_as_float(tau);
   const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
+  __shared__ int band_i[kDenseBand];
+  __shared__ float band_v[kDenseBand];
+  __shared__ int n_band, n_above, short_ok;
+  __shared__ uint32_t short_tau;
+  __shared__ int short_quota;
+  if (tid == 0) n_band = n_above = short_ok = 0;
+  __syncthreads();
   for (int64_t i0 = tid; i0 < E; i0 += 4 * kTopkThreads) {  // four independent loads in flight
     float v[4];
 #pragma unroll
@@ -67,15 +84,68 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t i = i0 + (int64_t)u * kTopkThreads;
-      if (v[u] >= lo && v[u] <= hi)
-        cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row,
-                                    S + i, g_lo, g_hi);
+      const bool above = v[u] > hi;
+      const unsigned long long bal = __ballot(above);
+      if ((tid & 63) == 0 && bal) atomicAdd(&n_above, __popcll(bal));
+      if (v[u] >= lo && v[u] <= hi) {
+        const int t = atomicAdd(&n_band, 1);
+        if (t < kDenseBand) band_i[t] = (int)i;
+      }
+    }
+  }
+  __syncthreads();
+  const int nb = n_band, r = k - n_above;
+  bool general = nb > kDenseBand || r < 1 || r > nb;
+  if (!general) {
+    for (int t = tid; t < nb; t += kTopkThreads) {
+      const int i = band_i[t];
+      const float v = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row,
+                                        S + i, g_lo, g_hi);
+      band_v[t] = v;
+      cand[i] = v;
+    }
+    __syncthreads();
+    for (int t = tid; t < nb; t += kTopkThreads) {
+      const float v = band_v[t];
+      const int i = band_i[t];
+      int rank = 0, greater = 0;
+      for (int u = 0; u < nb; ++u) {
+        greater += band_v[u] > v;
+        rank += band_v[u] > v || (band_v[u] == v && band_i[u] < i);
+      }
+      if (rank == r - 1 && v > lo && v < hi) {  // the threshold element, strictly inside the band
+        short_tau = __float_as_uint(v);
+        short_quota = r - greater;
+        short_ok = 1;
+      }
+    }
+    __syncthreads();
+    general = !short_ok;
+    if (!general) {
+      tau = short_tau;
+      quota = short_quota;
+    }
+  } else {
+    for (int64_t i0 = tid; i0 < E; i0 += 4 * kTopkThreads) {
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t i = i0 + (int64_t)u * kTopkThreads;
+        v[u] = i < E ? cand[i] : -1.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t i = i0 + (int64_t)u * kTopkThreads;
+        if (v[u] >= lo && v[u] <= hi)
+          cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row,
+                                      S + i, g_lo, g_hi);
+      }
     }
   }
   __syncthreads();
 
-  // 3. exact threshold on the patched scores
-  radix_select(sh, cand, E, k, false, &tau, &quota);
+  // 3. general route: exact threshold by a radix select over the patched scores
+  if (general) radix_select(sh, cand, E, k, false, &tau, &quota);
 
   // 4. ordered compaction
   int run_gt = 0, run_eq = 0;
