@@ -398,8 +398,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
 
 // bf16 decode with BOTH products on the matrix cores.  q.K as in decode_mfma_kernel.  The softmax
 // weights of a 32-token block are rounded to bf16 (as the values are) and written to LDS as
-// P[head][token]; V goes through the wave's staging buffer like K, and a lane assembles the MFMA B
-// operand V[8 tokens][its dim] from 8 dword reads (one per token, two dims each) and 4 byte permutes.
+// P[head][token]; V goes through the wave's staging buffer like K, and a lane gets the MFMA B operand
+// V[8 tokens][its dim] with two transposed LDS reads (ds_read_b64_tr_b16: lane s of a 16-lane group
+// addresses 4 dims of token s / 4 and receives dim s of 4 tokens).
 // out[head][dim] accumulates in one 16x16 tile per 16 dims, rows = heads, so the accumulator does not
 // grow with the group size and the vector ALU no longer does G x head_dim multiply-adds per token.
 __device__ __forceinline__ uint32_t bf16_rne(float f) {  // finite, non-negative input
@@ -417,7 +418,6 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   constexpr int NACC = NT > TILES ? NT / TILES : 1;      // q.K accumulators per block
   constexpr int NDT = D / 16;                            // output tiles (16 dims each)
   constexpr int ROWB = D * 2;
-  constexpr int VSW = CH == 16 ? 2 : 1;                  // V staging swizzle: chunk ^= (token / 8) << VSW
   constexpr int kThreads = NW * 64;
   static_assert(GPAD * D * 4 <= BT * CH * 16, "accumulators fit the staging buffers");
 
@@ -457,7 +457,6 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   for (int nd = 0; nd < NDT; ++nd) acc[nd] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   uint4* buf = kbuf[wave];
-  uint32_t* buf32 = reinterpret_cast<uint32_t*>(buf);
   reinterpret_cast<uint4*>(&pT[wave][0][0])[lane] = make_uint4(0u, 0u, 0u, 0u);  // rows of absent heads stay 0
   const int nblk = (t_end - t_begin + BT - 1) / BT;
   uint4 kv[NLOAD], vv[NLOAD];
@@ -486,9 +485,9 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   }
   __syncthreads();
 
-  // this lane's part of the V operand: dims 16 * nd + n, tokens 8j .. 8j+7 of the block (token / 8 = j)
-  const uint32_t v_sel = (n & 1) ? 0x07060302u : 0x05040100u;  // high or low halves of two dwords
-  const int v_lane = (8 * j) * CH * 4 + ((n & 7) >> 1);      // dword index of token 8j, chunk 0
+  // V staging swizzle (16-byte chunk ^= vswz(token)): the four tokens a 16-lane group reads together
+  // land in different banks
+  auto vswz = [](int t) { return CH == 16 ? (((t & 3) << 1) | (((t >> 3) & 1) << 3)) : ((t & 3) << 1); };
 
   for (int b = wave; b < nblk; b += NW) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // last block's reads of the buffer are done
@@ -559,7 +558,7 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int t = i * TPL + tq;
-      buf[t * CH + (cl ^ (((t >> 3) & 3) << VSW))] = vv[i];
+      buf[t * CH + (cl ^ vswz(t))] = vv[i];
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     if (more) load_block(b + NW, vv, Vr, vn);
@@ -570,15 +569,18 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
     for (int nd = 0; nd < NDT; ++nd) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[nd][r] *= corr[r];  // rows 4j + r are heads hbase + r for every j in use
-      const int chunk = (2 * nd + (n >> 3)) ^ (j << VSW);
-      uint32_t w[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) w[u] = buf32[v_lane + u * CH * 4 + chunk * 4];
-      uint4 vb;
-      vb.x = __builtin_amdgcn_perm(w[1], w[0], v_sel);
-      vb.y = __builtin_amdgcn_perm(w[3], w[2], v_sel);
-      vb.z = __builtin_amdgcn_perm(w[5], w[4], v_sel);
-      vb.w = __builtin_amdgcn_perm(w[7], w[6], v_sel);
+      // transposed LDS read: lane s of a 16-lane group gives the address of 4 dims of token s / 4
+      // and receives its own dim of 4 tokens
+      typedef short v4s_t __attribute__((ext_vector_type(4)));
+      const int tu = 8 * j + (n >> 2);                       // first token this lane addresses
+      const int cch = (2 * nd + ((n & 3) >> 1)) ^ vswz(tu);  // vswz(tu) = vswz(tu + 4)
+      const unsigned short* b16 = reinterpret_cast<const unsigned short*>(buf);
+      const v4s_t x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) v4s_t*)(b16 + (tu * CH + cch) * 8 + (n & 1) * 4));
+      const v4s_t x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) v4s_t*)(b16 + ((tu + 4) * CH + cch) * 8 + (n & 1) * 4));
+      struct { v4s_t a, b; } pair = {x0, x1};
+      const uint4 vb = __builtin_bit_cast(uint4, pair);
       acc[nd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pa), __builtin_bit_cast(bf16x8_t, vb),
                                                         acc[nd], 0, 0, 0);
     }
