@@ -154,3 +154,41 @@ def test_C4_per_query_paper_budget_full(ref):
         for g in range(G):
             cut = lambda a: np.concatenate([a[..., :S], a[..., S + g * k:S + (g + 1) * k], a[..., S + G * k:]], axis=-1)
             gu.check_kept(cut(got), cut(kept_r.reshape(Hkv, Bt)), s_r[0][:, g], S, W, k)
+
+
+def test_C5_length_dense_path(ref):
+    """The dense path (every token's score written, multi-workgroup histograms, 4-pass top-k) at the
+    longest configured row, L = 524288, on two layers; kept sets and scores against the oracle."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    cfg = synth.CONFIGS["C5"].with_(n_layers=2)
+    S, W, k, Bt = cfg.n_sink, cfg.n_recent, cfg.k, cfg.budget
+    P, Hkv, d, L = cfg.n_problems, cfg.n_kv_heads, cfg.head_dim, cfg.L
+    q_last, K, V, pos = synth.kv_device(cfg)
+    desc = sk.select_desc(q_last, K, V, S, W, k, Bt)
+    ws = torch.empty(sk.sagekv_select_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    Kc = torch.zeros((P, Hkv, Bt, d), dtype=K.dtype, device="cuda")
+    Vc = torch.zeros_like(Kc)
+    kept = torch.full((P, Hkv, Bt), -1, dtype=torch.int32, device="cuda")
+    scores = torch.empty((P, Hkv, L), dtype=torch.float32, device="cuda")
+    sk.sagekv_select(desc, q_last, K, V, Kc, Vc, kept, scores, ws)
+    torch.cuda.synchronize()
+    assert sk.sagekv_select_redone_rows(desc, ws) == -1
+    qh = synth.q_last_host(cfg)
+    _, nrows = synth.needles(cfg, qh)
+    p = 1
+    Kp, Vp = host_problem(cfg, p, pos, nrows)
+    Kc_r, Vc_r, kept_r, s_r = ref.select(cfg.dtype, GROUP_SUM, qh[p:p + 1], Kp, Vp, S, W, k, want_scores=True)
+    gu.check_scores(scores[p:p + 1].cpu().numpy(), s_r[:, :, 0])
+    n_ex = gu.check_kept(kept[p].cpu().numpy(), kept_r, s_r[:, :, 0], S, W, k)
+    if n_ex == 0:
+        np.testing.assert_array_equal(synth.torch_to_host(Kc[p:p + 1], cfg.dtype), Kc_r)
+        np.testing.assert_array_equal(synth.torch_to_host(Vc[p:p + 1], cfg.dtype), Vc_r)
+    # the pre-filtered pass over the same cache keeps the same tokens
+    sk.sagekv_select(desc, q_last, K, V, Kc, Vc, torch.zeros_like(kept), None, ws)
+    kept2 = torch.zeros_like(kept)
+    sk.sagekv_select(desc, q_last, K, V, Kc, Vc, kept2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(kept2, kept)
