@@ -25,6 +25,7 @@ namespace {
 
 constexpr int kMaxBand = 1024;  // candidates re-scored in fp64 per row on the fast path
 constexpr int kFastMaxG = 16;
+constexpr float kHeavyShare = 0.01f;  // see sample_stats_kernel (0.3 % and 0.1 % measured worse)
 
 // Per row: approximate softmax statistics from the sampled logits, approximate scores of the
 // sampled candidates, and their rank-th largest value = the row's filter threshold.
@@ -86,8 +87,40 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
       for (int w = 0; w < kTopkWaves; ++w)
         zz += (red[w][tid].x == -INFINITY) ? 0.f : red[w][tid].y * exp_fast(red[w][tid].x - M);
       sM[tid] = M;
+      sInv[tid] = zz;  // first estimate of Z^, refined below
+    }
+    __syncthreads();
+    // Second pass: a sampled token that would alone stand for more than 1 % of the head's mass is a
+    // heavy token, and heavy tokens are rare: it is counted once, not once per token it was meant
+    // to represent.  (Attention mass sits on few tokens; scaling such a token up by the sampling
+    // rate would put the head's normaliser off by a large factor and the row could not be
+    // certified.  Under-counting only lets a few more candidates through.)
+#pragma unroll
+    for (int g = 0; g < kFastMaxG; ++g) z[g] = 0.f;
+    for (int s = tid; s < n_slots; s += kTopkThreads) {
+      const float w = weight(s);
+      if (w > 0.f) {
+#pragma unroll
+        for (int g = 0; g < kFastMaxG; ++g)
+          if (g < G) {
+            const float e = exp_fast(slog[(int64_t)s * Gs + g] - sM[g]);
+            z[g] += (w * e > kHeavyShare * sInv[g] ? 1.f : w) * e;
+          }
+      }
+    }
+    __syncthreads();  // every thread has read the first estimates
+#pragma unroll
+    for (int g = 0; g < kFastMaxG; ++g)
+      if (g < G) {
+        const float zz = group_sum<64>(z[g]);
+        if (lane == 0) red[wave][g].y = zz;
+      }
+    __syncthreads();
+    if (tid < G) {
+      float zz = 0.f;
+      for (int w = 0; w < kTopkWaves; ++w) zz += red[w][tid].y;
       sInv[tid] = 1.0f / zz;
-      p.samp_stats[(int64_t)row * G + tid] = make_float2(M, 1.0f / zz);
+      p.samp_stats[(int64_t)row * G + tid] = make_float2(sM[tid], 1.0f / zz);
     }
   }
   __syncthreads();

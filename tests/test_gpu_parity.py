@@ -197,10 +197,10 @@ def test_prefilter_falls_back_when_all_scores_tie(ref):
 
 @pytest.mark.parametrize("sampled", [True, False])
 def test_prefilter_with_one_token_carrying_most_of_the_mass(ref, sampled):
-    """One candidate holds ~70% of head 0's attention.  If the strided sample contains it, the
-    sample counts it ~40 times, the sampled normaliser is far too large, the bound on dropped
-    tokens exceeds the k-th score and the row must be redone densely.  If the sample misses it the
-    filter is merely more permissive and the row is certified.  Either way the result is exact."""
+    """One candidate holds ~70% of head 0's attention.  Scaled up by the sampling rate it would make
+    the sampled normaliser ~40 times too large; the sampler counts a token that would stand for more
+    than 1 % of a head's mass once, so the row is certified whether the sample contains the token or
+    misses it (then the filter is merely more permissive).  Either way the result is exact."""
     P, Hq, Hkv, d, L, S, W, k = 1, 4, 1, 128, 40000, 4, 64, 500
     q, K, V = rand_case(21, P, Hq, Hkv, d, L, BF16)
     E = L - S - W
@@ -210,8 +210,26 @@ def test_prefilter_with_one_token_carrying_most_of_the_mass(ref, sampled):
     q64 = synth.to_f64(q[0, 0], BF16)
     K[0, 0, t] = synth.round_to_dtype(12.0 * q64 / np.linalg.norm(q64), BF16)  # logit ~ 12
     out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
-    assert out["redone"] == (1 if sampled else 0)
+    assert out["redone"] == 0
     assert t in out["kept"][0, 0].tolist()
+
+
+def test_prefilter_certifies_heavy_tailed_attention(ref):
+    """Queries scaled so that the logits have a standard deviation of ~2.5: the 100 heaviest of 65536
+    tokens hold about a quarter of a head's attention, as in a trained model.  Before heavy sampled
+    tokens were counted once, one row in seven of such a cache could not be certified."""
+    P, Hq, Hkv, d, L, S, W, k = 2, 16, 4, 128, 65536, 4, 256, 1788
+    q, K, V = rand_case(77, P, Hq, Hkv, d, L, BF16)
+    q = synth.round_to_dtype(2.5 * synth.to_f64(q, BF16), BF16)
+    Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    top100 = np.sort(s[0, 0, 0].astype(np.float64))[::-1][:100].sum() / Hq * Hkv
+    assert top100 > 0.1, top100  # the summed score of 4 heads: a share above 10 % of its total mass
+    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=False)
+    assert out["redone"] == 0
+    n_ex = gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k)
+    if n_ex == 0:
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
 
 
 def test_select_C2_shape_two_layers(ref):
