@@ -338,6 +338,42 @@ def test_invalid_arguments_are_rejected_before_launch():
     with pytest.raises(sk.SagekvError) as e:
         call(good, ws[:1024])
     assert e.value.code == 3
+    with pytest.raises(sk.SagekvError) as e:
+        sk.sagekv_select(good, q, None, K, Kc, Kc, kept, None, ws)  # null required pointer
+    assert e.value.code == 1
+
+    # decode calls
+    dd = sk.decode_desc(1, 4, 2, 128, sk.BF16, 4, 64, 32, 100)
+    dws = torch.empty(max(sk.sagekv_decode_workspace_bytes(dd), 16), dtype=torch.uint8, device="cuda")
+    out = torch.full((1, 4, 128), -7.0, dtype=torch.float32, device="cuda")
+    kn = torch.zeros((1, 2, 128), dtype=torch.bfloat16, device="cuda")
+    sk.sagekv_decode_step(dd, q, kn, kn, Kc, Kc.clone(), 0, out, dws)
+    torch.cuda.synchronize()
+    out.fill_(-7.0)
+
+    def code_of(fn):
+        try:
+            fn()
+        except sk.SagekvError as e:
+            return e.code
+        return 0
+
+    assert code_of(lambda: sk.sagekv_decode_attn(dd, q, Kc, Kc, 0, out, dws)) == 1            # len < 1
+    assert code_of(lambda: sk.sagekv_decode_attn(dd, q, Kc, Kc, 101, out, dws)) == 1          # len > capacity
+    assert code_of(lambda: sk.sagekv_decode_attn(dd, None, Kc, Kc, 10, out, dws)) == 1        # null query
+    assert code_of(lambda: sk.sagekv_decode_attn_window(dd, q, None, Kc, Kc, 10, out, dws)) == 1   # null sink query
+    assert code_of(lambda: sk.sagekv_decode_step(dd, q, kn, kn, Kc, Kc, -1, out, dws)) == 1   # negative counter
+    long_row = sk.decode_desc(1, 4, 2, 128, sk.BF16, 4, 900, 32, 1000)  # long enough to be split: needs scratch
+    Kl = torch.zeros((1, 2, 1000, 128), dtype=torch.bfloat16, device="cuda")
+    assert sk.sagekv_decode_workspace_bytes(long_row) > 8
+    assert code_of(lambda: sk.sagekv_decode_step(long_row, q, kn, kn, Kl, Kl, 0, out, dws[:8])) == 3  # too small
+    assert code_of(lambda: sk.sagekv_decode_step(long_row, q, kn, kn, Kl, Kl, 0, out, None)) == 3     # missing
+    grow = sk.decode_desc(1, 4, 2, 128, sk.BF16, 4, 64, 32, 100, True)
+    assert code_of(lambda: sk.sagekv_decode_step(grow, q, kn, kn, Kc, Kc, 0, out, dws)) == 1  # grown row exceeds capacity
+    bad = sk.decode_desc(1, 4, 2, 96, sk.BF16, 4, 64, 32, 100)
+    assert code_of(lambda: sk.sagekv_decode_attn(bad, q, Kc, Kc, 10, out, dws)) == 2          # head_dim
+    torch.cuda.synchronize()
+    assert float(out.max()) == -7.0  # nothing written
 
 
 # ----------------------------------------------------------------------------- decode
