@@ -66,6 +66,7 @@ def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
     import synth
     from oracle import ref
 
+    n_layers = min(n_layers, cfg.n_layers)
     sub = cfg.with_(n_layers=n_layers)
     q = synth.q_last_host(cfg)[: sub.n_problems].copy()
     pos, nrows = synth.needles(sub, q)
