@@ -61,7 +61,8 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   f.rank = (int)ceil(x * x);
   // Room for the candidates: about rank * wB tokens pass a list's threshold, 4 sigma high side
   // (rank + 4 sqrt(rank)) * wB; per-query lists share one candidate list per row (their union).
-  const double high = ((double)f.rank + 4.0 * sqrt((double)f.rank)) * (double)f.wB;
+  // (a heavy-tailed row may raise its rank to twice the planned one, see sample_stats_kernel)
+  const double high = (2.0 * (double)f.rank + 4.0 * sqrt(2.0 * (double)f.rank)) * (double)f.wB;
   const double planned = 2.5 * (double)d->k;
   int64_t cap = (int64_t)ceil(high > planned ? high : planned) * lists + 4096;
   f.cap = (int)(cap < E ? cap : E);

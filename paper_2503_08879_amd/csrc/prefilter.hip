@@ -32,7 +32,7 @@ constexpr float kHeavyShare = 0.01f;  // see sample_stats_kernel (0.3 % and 0.1 
 __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams p) {
   __shared__ TopkShared sh;
   __shared__ float2 red[kTopkWaves][kFastMaxG];
-  __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
+  __shared__ float sM[kFastMaxG], sInv[kFastMaxG], sHeavy[kFastMaxG];
   __shared__ float ss[8192];  // approximate scores of the sampled candidates
 
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -62,12 +62,18 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
       const float w = weight(s);
       if (w > 0.f) {
 #pragma unroll
-        for (int g = 0; g < kFastMaxG; ++g)
-          if (g < G) {
-            const float x = slog[(int64_t)s * Gs + g];
-            const float mn = fmaxf(m[g], x);
-            z[g] = z[g] * exp_fast(m[g] - mn) + w * exp_fast(x - mn);
-            m[g] = mn;
+        for (int g4 = 0; g4 < kFastMaxG; g4 += 4)
+          if (g4 < G) {  // rows of samp_logit are padded to a multiple of 4 heads: 16-byte loads
+            const float4 v = *reinterpret_cast<const float4*>(slog + (int64_t)s * Gs + g4);
+            const float xs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (g4 + e < G) {
+                const int g = g4 + e;
+                const float mn = fmaxf(m[g], xs[e]);
+                z[g] = z[g] * exp_fast(m[g] - mn) + w * exp_fast(xs[e] - mn);
+                m[g] = mn;
+              }
           }
       }
     }
@@ -95,16 +101,26 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
     // to represent.  (Attention mass sits on few tokens; scaling such a token up by the sampling
     // rate would put the head's normaliser off by a large factor and the row could not be
     // certified.  Under-counting only lets a few more candidates through.)
+    float zh[kFastMaxG];  // what the heavy tokens had added to the first estimate
 #pragma unroll
-    for (int g = 0; g < kFastMaxG; ++g) z[g] = 0.f;
+    for (int g = 0; g < kFastMaxG; ++g) z[g] = zh[g] = 0.f;
     for (int s = tid; s < n_slots; s += kTopkThreads) {
       const float w = weight(s);
       if (w > 0.f) {
 #pragma unroll
-        for (int g = 0; g < kFastMaxG; ++g)
-          if (g < G) {
-            const float e = exp_fast(slog[(int64_t)s * Gs + g] - sM[g]);
-            z[g] += (w * e > kHeavyShare * sInv[g] ? 1.f : w) * e;
+        for (int g4 = 0; g4 < kFastMaxG; g4 += 4)
+          if (g4 < G) {
+            const float4 v = *reinterpret_cast<const float4*>(slog + (int64_t)s * Gs + g4);
+            const float xs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (g4 + i < G) {
+                const int g = g4 + i;
+                const float e = exp_fast(xs[i] - sM[g]);
+                const bool heavy = w * e > kHeavyShare * sInv[g];
+                z[g] += (heavy ? 1.f : w) * e;
+                zh[g] += heavy ? w * e : 0.f;
+              }
           }
       }
     }
@@ -113,17 +129,35 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
     for (int g = 0; g < kFastMaxG; ++g)
       if (g < G) {
         const float zz = group_sum<64>(z[g]);
-        if (lane == 0) red[wave][g].y = zz;
+        const float hh = group_sum<64>(zh[g]);
+        if (lane == 0) red[wave][g] = make_float2(hh, zz);
       }
     __syncthreads();
     if (tid < G) {
-      float zz = 0.f;
-      for (int w = 0; w < kTopkWaves; ++w) zz += red[w][tid].y;
+      float zz = 0.f, hh = 0.f;
+      for (int w = 0; w < kTopkWaves; ++w) {
+        hh += red[w][tid].x;
+        zz += red[w][tid].y;
+      }
+      sHeavy[tid] = hh / sInv[tid];  // share of the first estimate that came from heavy tokens
       sInv[tid] = 1.0f / zz;
       p.samp_stats[(int64_t)row * G + tid] = make_float2(sM[tid], 1.0f / zz);
     }
   }
   __syncthreads();
+  // A heavy-tailed row (the sample met heavy tokens) has heads whose normalisers are known with
+  // very different accuracy, whatever the sampler does about the heavy tokens it saw: some head
+  // has others it did not see.  The summed score then needs a threshold further down: the rank
+  // grows with the largest heavy share, up to twice the planned one (the candidate capacity is
+  // planned for that).  Per-query lists do not need it: a head's own scale cancels.
+  int rank = p.rank;
+  if (p.n_lists == 1) {
+    float h = 0.f;
+    for (int g = 0; g < G; ++g) h = fmaxf(h, sHeavy[g]);
+    const float grow = fminf(1.f, 4.f * fmaxf(0.f, h - 0.04f));
+    rank = (int)((float)p.rank * (1.f + grow));
+    if (rank > nB) rank = nB;
+  }
 
   // group-sum: one threshold on the summed approximate score; per-query: one per head on its own
   for (int li = 0; li < p.n_lists; ++li) {
@@ -132,15 +166,27 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
     for (int s = tid; s < nB; s += kTopkThreads) {
       const float* lg = slog + (int64_t)(64 * p.nA + s) * Gs;
       float a = 0.f;
-      for (int g = g_lo; g < g_hi; ++g) a += exp_fast(lg[g] - sM[g]) * sInv[g];
+      if (p.n_lists > 1) {
+        a = exp_fast(lg[g_lo] - sM[g_lo]) * sInv[g_lo];
+      } else {
+#pragma unroll
+        for (int g4 = 0; g4 < kFastMaxG; g4 += 4)
+          if (g4 < G) {
+            const float4 v = *reinterpret_cast<const float4*>(lg + g4);
+            const float xs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (g4 + i < G) a += exp_fast(xs[i] - sM[g4 + i]) * sInv[g4 + i];
+          }
+      }
       ss[s] = a;
     }
     __syncthreads();
     float tau_f = 0.f;  // rank beyond the sample: everything passes (the row is then redone densely)
-    if (p.rank >= 1 && p.rank <= nB) {
+    if (rank >= 1 && p.rank <= nB) {
       uint32_t tau;
       int quota;
-      radix_select(sh, ss, nB, p.rank, false, &tau, &quota);
+      radix_select(sh, ss, nB, rank, false, &tau, &quota);
       tau_f = __uint_as_float(tau);
     }
     if (tid == 0) p.samp_tau[(int64_t)row * p.n_lists + li] = tau_f;
