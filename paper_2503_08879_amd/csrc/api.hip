@@ -43,7 +43,9 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   f.stepB = ((E - 16) << 16) / (4 * f.nB - 1);  // between 16-token runs
   f.nA = d->n_sink > 0 ? 1 : 0;
   f.validA = d->n_sink < 64 ? d->n_sink : 64;
-  f.nC = d->n_recent >= 256 ? 4 : (d->n_recent + 63) / 64;
+  // the recent window is where a trained model puts much of its attention: up to its last 512 tokens
+  // are all sampled
+  f.nC = d->n_recent >= 512 ? 8 : (d->n_recent + 63) / 64;
   f.validC = d->n_recent < 64 * f.nC ? d->n_recent : 64 * f.nC;
   f.wA = f.nA ? (float)d->n_sink / (float)f.validA : 0.f;
   f.wB = (float)E / (float)(64 * f.nB);
