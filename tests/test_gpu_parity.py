@@ -234,6 +234,37 @@ def test_prefilter_certifies_heavy_tailed_attention(ref, scale, share):
         np.testing.assert_array_equal(out["Vc"], Vc)
 
 
+def test_prefilter_certifies_model_like_attention(ref):
+    """An attention profile shaped like a trained model's: eight very heavy first tokens (four of them
+    outside the sink, among the candidates), a recent window with an exponential bump, a heavy-tailed
+    middle.  The pre-filtered path must certify every row and agree with the oracle."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 65536, 4, 256, 1788
+    G = Hq // Hkv
+    q, K, V = rand_case(78, P, Hq, Hkv, d, L, BF16)
+    q64 = 2.5 * synth.to_f64(q, BF16)
+    q = synth.round_to_dtype(q64, BF16)
+    K64 = synth.to_f64(K, BF16)
+    qdir = q64.reshape(P, Hkv, G, d).mean(2)
+    qdir /= np.linalg.norm(qdir, axis=-1, keepdims=True)
+    boost = np.zeros(L)
+    boost[:8] = 10.0
+    t = np.arange(L - 2048, L)
+    boost[t] += 4.0 * np.exp(-(L - 1 - t) / 512.0)
+    unit = np.sqrt(G) / 2.5   # key displacement along qdir for about one unit of logit
+    K64 += boost[None, None, :, None] * unit * qdir[:, :, None, :]
+    K = synth.round_to_dtype(K64, BF16)
+    Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    row = s[0, 0, 0].astype(np.float64)
+    assert row[:8].sum() / G > 0.05 and row[L - W:].sum() / G > 0.01  # the profile is what it says
+    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=False)
+    assert out["redone"] == 0
+    n_ex = gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k)
+    assert set(range(4, 8)) <= set(out["kept"][0, 0].tolist())  # the heavy candidates are kept
+    if n_ex == 0:
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
+
+
 def test_select_C2_shape_two_layers(ref):
     """Config C2's row shape (32q/8kv, d128, bf16, L 32768, 4+1788+256) on 2 of its 32 layers."""
     cfg = synth.CONFIGS["C2"].with_(n_layers=2)
