@@ -10,7 +10,8 @@
  *   - Every data pointer is DEVICE memory owned by the caller (unless a comment
  *     says host).  Descriptors are host structs, read during the call only.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, null =
- *     the default stream).  No call allocates, frees or synchronises.
+ *     the default stream).  No call allocates, frees or synchronises (the two benchmark aids
+ *     that wait for the stream say so).
  *   - Indices are 0-based.  A "problem" is one layer of one sequence; problems are
  *     independent (Sec. 2: selection is done "for each layer").  A "row" is one
  *     (problem, KV head).  G = n_q_heads / n_kv_heads consecutive query heads share
@@ -158,7 +159,9 @@ size_t sagekv_decode_workspace_bytes(const sagekv_decode_desc* desc);
 
 /* Step 4's attention: out[h] = sum_t softmax_t( q[h] . Kc[c][t] / sqrt(head_dim) ) Vc[c][t],
  * t in [0, len), c = h / G.   q [n_problems, Hq, head_dim]; out [n_problems, Hq, head_dim] fp32.
- * 1 <= len <= compact_capacity. */
+ * 1 <= len <= compact_capacity.  Logits, softmax and the weighted sum are fp32; with a bf16 cache
+ * and more than 4 heads per KV head, or a row split over several workgroups, the softmax weights
+ * are rounded to bf16 (like the values they multiply) and the sum runs on the matrix cores. */
 sagekv_status sagekv_decode_attn(const sagekv_decode_desc* desc, const void* q, const void* Kc, const void* Vc,
                                  int32_t len, float* out, void* workspace, size_t workspace_bytes,
                                  void* hip_stream);
