@@ -41,3 +41,39 @@ def test_status_strings_and_host_side_checks():
     assert sk.binding.lib().sagekv_decode_attn(ctypes.byref(dd), None, None, None, 10, None, None, 0, None) == 1
     dd.compact_capacity = 100
     assert sk.sagekv_decode_workspace_bytes(dd) == 0
+
+
+def test_header_is_plain_c_and_a_c_program_links(tmp_path):
+    """The boundary is usable from C: the header compiles as strict C99, and a C program that calls the
+    host-only entry points links against the library and runs without a GPU.  The struct sizes seen by
+    C are those the ctypes binding marshals."""
+    import subprocess
+
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "sagekv.h"
+int main(void) {
+  sagekv_select_desc d = {0};
+  d.n_problems = 32; d.n_q_heads = 32; d.n_kv_heads = 8; d.head_dim = 128; d.dtype = SAGEKV_BF16;
+  d.head_mode = SAGEKV_HEADS_GROUP_SUM; d.L = 131072;
+  d.k_stride_problem = d.v_stride_problem = 8LL * 131072 * 128;
+  d.k_stride_head = d.v_stride_head = 131072LL * 128; d.k_stride_token = d.v_stride_token = 128;
+  d.n_sink = 4; d.n_recent = 512; d.k = 3580; d.compact_capacity = 4096;
+  sagekv_decode_desc dd = {32, 32, 8, 128, SAGEKV_BF16, SAGEKV_HEADS_GROUP_SUM, 4, 3580, 512, 4096, 0};
+  printf("%zu %zu %zu %zu %zu %s\n", sizeof(sagekv_select_desc), sizeof(sagekv_decode_desc), sizeof(sagekv_paged_kv),
+         sagekv_select_workspace_bytes(&d), sagekv_decode_workspace_bytes(&dd), sagekv_status_string(SAGEKV_ERR_WORKSPACE));
+  return sagekv_select(&d, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == SAGEKV_ERR_INVALID_ARG ? 0 : 1;
+}
+''')
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.dirname(sk.binding.LIB_PATH)
+    exe = tmp_path / "abi"
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, str(src), "-o", str(exe),
+                           "-L", libdir, "-lsagekv", f"-Wl,-rpath,{libdir}"])
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=5)
+    assert [int(x) for x in out[:3]] == [ctypes.sizeof(sk.SelectDesc), ctypes.sizeof(sk.DecodeDesc), ctypes.sizeof(sk.PagedKV)]
+    assert int(out[3]) == sk.sagekv_select_workspace_bytes(sk.SelectDesc(
+        32, 32, 8, 128, 0, 0, 131072, 8 * 131072 * 128, 131072 * 128, 128, 8 * 131072 * 128, 131072 * 128, 128,
+        4, 512, 3580, 4096, 0))
+    assert int(out[4]) == 0 and "workspace" in out[5]
