@@ -22,7 +22,9 @@
  *   - Errors are return codes.  Arguments are checked before anything is launched:
  *     on SAGEKV_ERR_INVALID_ARG / _UNSUPPORTED / _WORKSPACE nothing was written.
  *   - Element types: bf16 (raw 16-bit patterns) or fp32; head_dim 64 or 128; the
- *     innermost (head_dim) stride is 1 and rows must be 16-byte aligned.
+ *     innermost (head_dim) stride is 1 and rows must be 16-byte aligned: base pointers of
+ *     caches, queries and workspaces on 16 bytes (else SAGEKV_ERR_UNSUPPORTED), strides in
+ *     multiples of 16 bytes.
  */
 #ifndef SAGEKV_H
 #define SAGEKV_H

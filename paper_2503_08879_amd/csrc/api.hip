@@ -2,6 +2,7 @@
 #include "../../include/sagekv.h"
 
 #include <math.h>
+#include <stdint.h>
 
 #include <vector>
 
@@ -244,10 +245,16 @@ struct StageTimer {
 
 sagekv_status dev(hipError_t e) { return e == hipSuccess ? SAGEKV_OK : SAGEKV_ERR_DEVICE; }
 
+// Every cache and query row is read and written 16 bytes per lane.
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
 sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void* q_sink, const void* k_new,
                          const void* v_new,
                          void* Kc, void* Vc, int slot, int len, float* out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
+  if (!aligned16(q) || !aligned16(q_sink) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(Kc) ||
+      !aligned16(Vc) || ((uintptr_t)out & 3u) || !aligned16(ws))
+    return SAGEKV_ERR_UNSUPPORTED;
   const DecodeLayout l = decode_layout(d);
   if (l.total > 0 && (!ws || ws_bytes < l.total)) return SAGEKV_ERR_WORKSPACE;
   DecodeParams p;
@@ -317,6 +324,9 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
   sagekv_status st;
   if (!check_select(d, &st)) return st;
   if (!q_last || !K || !V || !Kc || !Vc || !kept_idx) return SAGEKV_ERR_INVALID_ARG;
+  if (!aligned16(q_last) || !aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc) ||
+      ((uintptr_t)kept_idx & 3u) || ((uintptr_t)scores_out & 15u) || !aligned16(workspace))
+    return SAGEKV_ERR_UNSUPPORTED;
   const SelectLayout l = select_layout(d, scores_out == nullptr);
   if (!workspace || workspace_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -570,6 +580,7 @@ sagekv_status sagekv_select_paged(const sagekv_select_desc* d, const sagekv_page
   sagekv_status st;
   if (!check_select(d, &st)) return st;
   if (!pg || !pg->block_table || pg->n_pages < 1) return SAGEKV_ERR_INVALID_ARG;
+  if ((uintptr_t)pg->block_table & 3u) return SAGEKV_ERR_UNSUPPORTED;
   const int ps = pg->page_size;
   if (ps < 16 || (ps & (ps - 1))) return SAGEKV_ERR_INVALID_ARG;
   if (pg->table_pitch < (d->L + ps - 1) / ps) return SAGEKV_ERR_INVALID_ARG;
@@ -610,6 +621,7 @@ sagekv_status sagekv_append(const sagekv_decode_desc* d, const void* k_new, cons
   sagekv_status st;
   if (!check_decode(d, &st)) return st;
   if (!k_new || !v_new || !Kc || !Vc || n_appended < 0) return SAGEKV_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(Kc) || !aligned16(Vc)) return SAGEKV_ERR_UNSUPPORTED;
   const int base = d->n_sink + decode_lists(d) * d->k;
   const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;

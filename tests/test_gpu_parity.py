@@ -374,6 +374,11 @@ def test_invalid_arguments_are_rejected_before_launch():
     with pytest.raises(sk.SagekvError) as e:
         sk.sagekv_select(good, q, None, K, Kc, Kc, kept, None, ws)  # null required pointer
     assert e.value.code == 1
+    flat = torch.zeros(K.numel() + 8, dtype=torch.bfloat16, device="cuda")
+    K_off = flat[1:1 + K.numel()].view(K.shape)  # same strides, base pointer 2 bytes off a 16-byte boundary
+    with pytest.raises(sk.SagekvError) as e:
+        sk.sagekv_select(good, q, K_off, K, Kc, Kc, kept, None, ws)
+    assert e.value.code == 2
 
     # decode calls
     dd = sk.decode_desc(1, 4, 2, 128, sk.BF16, 4, 64, 32, 100)
@@ -394,6 +399,8 @@ def test_invalid_arguments_are_rejected_before_launch():
     assert code_of(lambda: sk.sagekv_decode_attn(dd, q, Kc, Kc, 0, out, dws)) == 1            # len < 1
     assert code_of(lambda: sk.sagekv_decode_attn(dd, q, Kc, Kc, 101, out, dws)) == 1          # len > capacity
     assert code_of(lambda: sk.sagekv_decode_attn(dd, None, Kc, Kc, 10, out, dws)) == 1        # null query
+    q_off = torch.zeros(q.numel() + 8, dtype=torch.bfloat16, device="cuda")[3:3 + q.numel()].view(q.shape)
+    assert code_of(lambda: sk.sagekv_decode_attn(dd, q_off, Kc, Kc, 10, out, dws)) == 2       # misaligned query
     assert code_of(lambda: sk.sagekv_decode_attn_window(dd, q, None, Kc, Kc, 10, out, dws)) == 1   # null sink query
     assert code_of(lambda: sk.sagekv_decode_step(dd, q, kn, kn, Kc, Kc, -1, out, dws)) == 1   # negative counter
     long_row = sk.decode_desc(1, 4, 2, 128, sk.BF16, 4, 900, 32, 1000)  # long enough to be split: needs scratch
