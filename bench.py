@@ -41,7 +41,7 @@ def algorithmic_bytes(cfg, budget=None):
 def read_traffic(cfg_name, key="traffic_bytes_per_launch"):
     """HBM bytes per launch of the score kernel (or, with another key, of the decode kernel) from the
     committed rocprofv3 --pmc summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"score_kernel_{cfg_name}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg_name}_pmc.txt")
     if not os.path.exists(path):
         return None
     m = re.search(rf"^{key}:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
