@@ -128,6 +128,7 @@ struct TopkParams {
   int S, W, k;
   int n_lists;        // 1 or G; list g of a row ranks head g's own probabilities
   float band;  // relative half-width of the fp64 re-evaluation band around the k-th score
+  int bitmap_bytes;  // dynamic LDS of the launch (set by launch_topk): room for one bit per candidate, or 0
 };
 
 // The sample of the fast path, in blocks of 64 tokens (one wave-block of the MFMA kernels each):

@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   __shared__ int band_j[kMaxBand], band_tok[kMaxBand];
   __shared__ float band_v[kMaxBand];
   __shared__ int n_band, n_above, n_list;
-  extern __shared__ uint32_t bitmap[];  // one bit per eviction candidate of the row
+  extern __shared__ __align__(16) uint32_t bitmap[];  // one bit per eviction candidate of the row
 
   const int list = blockIdx.x, tid = threadIdx.x;  // one list per row, or one per (row, query head)
   const int row = list / p.n_lists, gl = list % p.n_lists;
@@ -371,22 +371,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   }
   __syncthreads();
 
-  int run = 0;
-  for (int w0 = 0; w0 < n_words; w0 += kTopkThreads) {
-    const int w = w0 + tid;
-    uint32_t word = w < n_words ? bitmap[w] : 0u;
-    const int cnt = __popc(word);
-    int tot;
-    const int incl = block_scan_incl<kTopkThreads>(cnt, sh.wave_tot, &tot);
-    int pos = run + incl - cnt;
-    while (word) {
-      const int b = __ffs(word) - 1;
-      word &= word - 1;
-      if (pos < k) kept[S + pos] = (int32_t)(S + w * 32 + b);
-      ++pos;
-    }
-    run += tot;
-  }
+  bitmap_compact(bitmap, n_words, S, kept + S, k, sh.wave_tot);
 }
 
 __global__ __launch_bounds__(kTopkThreads) void collect_failed_kernel(const int* row_fail, int rows, int* fail_list,

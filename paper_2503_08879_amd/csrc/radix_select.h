@@ -81,6 +81,40 @@ __device__ inline void radix_select(TopkShared& sh, const float* cand, int64_t E
   *quota = rem;
 }
 
+// Ordered output of a selection kept as a bitmap in LDS (16-byte aligned): writes first + (index of
+// the j-th set bit) to out[j] for j < k.  Every thread takes four consecutive words per round.
+__device__ inline void bitmap_compact(const uint32_t* bitmap, int n_words, int first, int32_t* out, int k,
+                                      int* wave_tot) {
+  int run = 0;
+  for (int w0 = 0; w0 < n_words; w0 += 4 * kTopkThreads) {
+    const int w = w0 + 4 * (int)threadIdx.x;
+    uint32_t word[4] = {0u, 0u, 0u, 0u};
+    if (w + 3 < n_words) {
+      const uint4 v = *reinterpret_cast<const uint4*>(bitmap + w);
+      word[0] = v.x, word[1] = v.y, word[2] = v.z, word[3] = v.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (w + j < n_words) word[j] = bitmap[w + j];
+    }
+    const int cnt = __popc(word[0]) + __popc(word[1]) + __popc(word[2]) + __popc(word[3]);
+    int tot;
+    const int incl = block_scan_incl<kTopkThreads>(cnt, wave_tot, &tot);
+    int pos = run + incl - cnt;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t x = word[j];
+      while (x) {
+        const int b = __ffs(x) - 1;
+        x &= x - 1;
+        if (pos < k) out[pos] = (int32_t)(first + (w + j) * 32 + b);
+        ++pos;
+      }
+    }
+    run += tot;
+  }
+}
+
 template <int DT>
 __device__ inline double elem_f64(const void* base, int64_t i);
 template <>

@@ -104,6 +104,25 @@ def test_select_no_candidates(ref):
     select_parity(ref, F32, q, K, V, 8, 32, 0)  # E = 0
 
 
+def test_select_tiny_rows_at_every_alignment(ref):
+    """Few candidates, every offset of the candidate range against the 16-byte loads of the dense
+    top-k (first candidate S = 0..3 floats into its score row, 1..9 candidates, odd row pitches)."""
+    for S in range(4):
+        for E in (1, 2, 3, 4, 5, 6, 7, 8, 9):
+            W = 2 + (S + E) % 3
+            L = S + E + W
+            q, K, V = rand_case(300 + 10 * S + E, 2, 4, 2, 64, L, F32)
+            for k in sorted({1, (E + 1) // 2, E}):
+                select_parity(ref, F32, q, K, V, S, W, k)
+
+
+def test_select_row_longer_than_the_lds_bitmap(ref):
+    """More than 512K candidates: the dense top-k writes its output with the two-pass route."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 2, 1, 64, 540001, 3, 50, 2000
+    q, K, V = rand_case(11, P, Hq, Hkv, d, L, BF16)
+    select_parity(ref, BF16, q, K, V, S, W, k)
+
+
 def test_select_all_scores_equal_takes_lowest_indices(ref):
     """q = 0: every probability is 1/L, the whole row ties; the first k candidates must win."""
     P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 6000, 4, 50, 700
