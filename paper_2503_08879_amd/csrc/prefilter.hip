@@ -193,7 +193,8 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
   }
 }
 
-template <int DT>
+// PQ: per-query lists (n_lists = G > 1), each list keeps its own compacted candidates.
+template <int DT, bool PQ>
 __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams p) {
   __shared__ TopkShared sh;
   __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
@@ -246,11 +247,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   // token the filter dropped (the row is only accepted if the k-th score's band lies above the
   // bound), and with per-query lists most of the row's shared candidates came in through other heads.
   const float bound = p.bound[list];
-  const bool compact = p.n_lists > 1;
+  constexpr bool compact = PQ;
   float* cs = p.cand_score + (int64_t)list * p.cap;
   int32_t* ci = p.cand_pos + (int64_t)list * p.cap;
   for (int d0 = 0; d0 < n_all; d0 += 4 * kTopkThreads) {
-    int64_t slot[4];
+    int64_t chunk_base[4];  // first slot of the candidate's score chunk, -1: past the end
+    int off[4];             // its slot within the chunk
 #pragma unroll
     for (int u = 0; u < 4; ++u) {  // independent lookups: their loads overlap
       const int dj = d0 + u * kTopkThreads + tid;
@@ -259,13 +261,42 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
         const int mid = (lo_c + hi_c) >> 1;
         if (chunk_off[mid] <= dj) lo_c = mid; else hi_c = mid;
       }
-      slot[u] = dj < n_all ? ((int64_t)row * p.n_chunks + lo_c) * kScoreChunk + (dj - chunk_off[lo_c]) : -1;
+      chunk_base[u] = dj < n_all ? ((int64_t)row * p.n_chunks + lo_c) * kScoreChunk : -1;
+      off[u] = dj < n_all ? dj - chunk_off[lo_c] : 0;
     }
+    if constexpr (compact) {  // per-query lists: only this list's head is read
+      float x[4];
+      int32_t ti[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t cb = chunk_base[u] < 0 ? (int64_t)row * p.n_chunks * kScoreChunk : chunk_base[u];
+        ti[u] = p.cand_idx[cb + off[u]];
+        x[u] = p.cand_logit[(cb + off[u]) * p.Gs + gl];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float a = 0.f;
+        a += exp_accurate(x[u] - sM[gl]) * sInv[gl];
+        const bool keep = chunk_base[u] >= 0 && a >= bound;
+        const unsigned long long bal = __ballot(keep);
+        if (bal) {  // wave-uniform
+          int base = 0;
+          if ((tid & 63) == 0) base = atomicAdd(&n_list, __popcll(bal));
+          base = __shfl(base, 0);
+          if (keep) {
+            const int pos = base + __popcll(bal & ((1ull << (tid & 63)) - 1ull));
+            cs[pos] = a;
+            ci[pos] = ti[u];
+          }
+        }
+      }
+    } else {
+    // one list per row: nearly every candidate reaches the bound, they stay in place
     float4 lg[4][kFastMaxG / 4];
     int32_t ti[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t sl = slot[u] < 0 ? (int64_t)row * p.n_chunks * kScoreChunk : slot[u];
+      const int64_t sl = chunk_base[u] < 0 ? (int64_t)row * p.n_chunks * kScoreChunk : chunk_base[u] + off[u];
       ti[u] = p.cand_idx[sl];
 #pragma unroll
       for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
@@ -274,36 +305,20 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int dj = d0 + u * kTopkThreads + tid;
-      float a = 0.f;
       if (dj < n_all) {
+        float a = 0.f;
 #pragma unroll
         for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
           if (g4 * 4 < G) {
             const float x[4] = {lg[u][g4].x, lg[u][g4].y, lg[u][g4].z, lg[u][g4].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (g4 * 4 + e >= g_lo && g4 * 4 + e < g_hi) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
+              if (g4 * 4 + e < G) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
           }
+        cs[dj] = a;
+        ci[dj] = ti[u];
       }
-      if (!compact) {  // one list per row: nearly every candidate reaches the bound, keep them in place
-        if (dj < n_all) {
-          cs[dj] = a;
-          ci[dj] = ti[u];
-        }
-        continue;
-      }
-      const bool keep = dj < n_all && a >= bound;
-      const unsigned long long bal = __ballot(keep);
-      if (bal) {  // wave-uniform
-        int base = 0;
-        if ((tid & 63) == 0) base = atomicAdd(&n_list, __popcll(bal));
-        base = __shfl(base, 0);
-        if (keep) {
-          const int pos = base + __popcll(bal & ((1ull << (tid & 63)) - 1ull));
-          cs[pos] = a;
-          ci[pos] = ti[u];
-        }
-      }
+    }
     }
   }
   __syncthreads();
@@ -410,12 +425,19 @@ hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s) {
   if (lds > 64 * 1024 || p.geo.G > kFastMaxG) return hipErrorInvalidValue;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)topk_cand_kernel<DT_BF16>,
+    hipError_t e = hipFuncSetAttribute((const void*)topk_cand_kernel<DT_BF16, false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)topk_cand_kernel<DT_BF16, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              64 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(topk_cand_kernel<DT_BF16>, dim3((unsigned)(rows * p.n_lists)), dim3(kTopkThreads), lds, s, p);
+  const dim3 grid((unsigned)(rows * p.n_lists));
+  if (p.n_lists > 1)
+    hipLaunchKernelGGL((topk_cand_kernel<DT_BF16, true>), grid, dim3(kTopkThreads), lds, s, p);
+  else
+    hipLaunchKernelGGL((topk_cand_kernel<DT_BF16, false>), grid, dim3(kTopkThreads), lds, s, p);
   return hipGetLastError();
 }
 
