@@ -222,12 +222,9 @@ def main():
         cfg = cfg.with_(n_q_heads=args.q_heads)
     head_mode, lists = sk.GROUP_SUM, 1
     if args.per_query_budget:
-        B, G = args.per_query_budget, cfg.G
-        kk = 1
-        while 2 * kk <= B // (2 * G):
-            kk *= 2
-        cfg = cfg.with_(n_sink=B // 4, k=kk, n_recent=B - B // 4 - G * kk)
-        head_mode, lists = sk.PER_QUERY, G
+        n_sink, kk, n_recent = sk.sagekv_paper_budget(args.per_query_budget, cfg.G)
+        cfg = cfg.with_(n_sink=n_sink, k=kk, n_recent=n_recent)
+        head_mode, lists = sk.PER_QUERY, cfg.G
         args.no_cpu_baseline = True
     n_dec = cfg.decode_steps if args.decode_steps is None else args.decode_steps
     torch.cuda.set_device(0)

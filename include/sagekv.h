@@ -198,6 +198,14 @@ sagekv_status sagekv_decode_step_window(const sagekv_decode_desc* desc, const vo
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char* sagekv_status_string(sagekv_status s); /* host string, static storage */
 
+/* The paper's split of a per-KV-head budget of B tokens for PER_QUERY selection (App. A.2):
+ * n_sink = B/4, k per query head = B/(2G) rounded down to a power of two (the two cases the
+ * appendix prints, G = 4 -> 1024 and G = 7 -> 512 at B = 8192, fix the rounding), n_recent =
+ * what is left, so that n_sink + G*k + n_recent = B.  Host only, touches no device.  G = query
+ * heads per KV head.  INVALID_ARG (outputs untouched) for null outputs, G < 1 or B < 4*G (no room
+ * for one token per head). */
+sagekv_status sagekv_paper_budget(int32_t B, int32_t G, int32_t* n_sink, int32_t* k, int32_t* n_recent);
+
 /* Stage timing for benchmarks (host-side state, per process; not thread safe).
  * sagekv_stage_timing_enable(n) creates HIP events for the next n instrumented calls of
  * sagekv_select and n of sagekv_decode_attn / sagekv_decode_step (n = 0 switches it off and

@@ -24,6 +24,7 @@ EXPORTS = (
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
     "sagekv_decode_attn_window", "sagekv_decode_step_window",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read", "sagekv_stage_timing_stages",
+    "sagekv_paper_budget",
 )
 
 
@@ -72,6 +73,8 @@ def lib():
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_08879_amd.build`")
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.sagekv_paper_budget.restype = ctypes.c_int
+        L.sagekv_paper_budget.argtypes = [i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.sagekv_status_string.restype = ctypes.c_char_p
         L.sagekv_status_string.argtypes = [ctypes.c_int]
         L.sagekv_select_workspace_bytes.restype = sz
@@ -103,6 +106,13 @@ def lib():
         L.sagekv_stage_timing_read.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float)]
         _lib = L
     return _lib
+
+
+def sagekv_paper_budget(B: int, G: int):
+    """(n_sink, k, n_recent) of the paper's budget split for PER_QUERY selection (App. A.2)."""
+    s, k, r = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().sagekv_paper_budget(B, G, ctypes.byref(s), ctypes.byref(k), ctypes.byref(r)), "sagekv_paper_budget")
+    return s.value, k.value, r.value
 
 
 def status_string(code: int) -> str:

@@ -297,6 +297,17 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
 
 extern "C" {
 
+sagekv_status sagekv_paper_budget(int32_t B, int32_t G, int32_t* n_sink, int32_t* k, int32_t* n_recent) {
+  if (!n_sink || !k || !n_recent || G < 1 || B < 4 * (int64_t)G) return SAGEKV_ERR_INVALID_ARG;
+  const int32_t share = B / (2 * G);  // >= 2
+  int32_t pow2 = 1;
+  while (pow2 <= share / 2) pow2 *= 2;
+  *n_sink = B / 4;
+  *k = pow2;
+  *n_recent = B - B / 4 - G * pow2;
+  return SAGEKV_OK;
+}
+
 const char* sagekv_status_string(sagekv_status s) {
   switch (s) {
     case SAGEKV_OK: return "ok";

@@ -16,7 +16,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert "sagekv_select" in names and "sagekv_decode_attn" in names and len(names) == 14
+    assert "sagekv_select" in names and "sagekv_decode_attn" in names and len(names) == 15
     lib = ctypes.CDLL(sk.binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -41,6 +41,30 @@ def test_status_strings_and_host_side_checks():
     assert sk.binding.lib().sagekv_decode_attn(ctypes.byref(dd), None, None, None, 10, None, None, 0, None) == 1
     dd.compact_capacity = 100
     assert sk.sagekv_decode_workspace_bytes(dd) == 0
+
+
+def test_paper_budget_matches_the_printed_splits_and_the_oracle(ref):
+    """Host-only call: the two splits the paper prints (App. A.2), the oracle's rule over a grid,
+    and the error cases."""
+    path = os.path.join(ROOT, "tests", "golden", "paper_budget.txt")
+    rows = [list(map(int, l.split())) for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 2
+    for B, G, sink, k, recent in rows:
+        assert sk.sagekv_paper_budget(B, G) == (sink, k, recent)
+    for G in (1, 2, 3, 4, 5, 7, 8, 16):
+        for B in (4 * G, 4 * G + 1, 100, 1000, 1024, 4096, 8192, 10000, 1 << 20):
+            if B < 4 * G:
+                continue
+            s, k, r = sk.sagekv_paper_budget(B, G)
+            assert (s, k, r) == ref.paper_budget(B, G)
+            assert s + G * k + r == B and k >= 1 and k & (k - 1) == 0 and r >= 0
+    i32 = ctypes.c_int32
+    a, b, c = i32(-7), i32(-7), i32(-7)
+    L = sk.binding.lib()
+    assert L.sagekv_paper_budget(8192, 0, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 1
+    assert L.sagekv_paper_budget(27, 7, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 1
+    assert L.sagekv_paper_budget(8192, 4, None, ctypes.byref(b), ctypes.byref(c)) == 1
+    assert (a.value, b.value, c.value) == (-7, -7, -7)
 
 
 def test_header_is_plain_c_and_a_c_program_links(tmp_path):
