@@ -2,8 +2,8 @@
 // per row, the k candidates with the largest score, ties to the lower index, written in
 // ascending position between the sink and the recent window; then the gather of K and V.
 //
-// topk_kernel: one 1024-thread workgroup per row; three passes over the row's scores, all with
-// aligned 16-byte loads.
+// topk_kernel: one 1024-thread workgroup per row; two passes over the row's scores (steps 1 and
+// 2) on the usual route, all with aligned 16-byte loads.
 //   1. coarse bracket of the k-th score: the first two digits (11 + 11 bits) of a radix select on
 //      the fp32 bit patterns of the scores (all positive, so the unsigned order is the float
 //      order).  The first digit's histogram was built by many workgroups in the combine stage; the
