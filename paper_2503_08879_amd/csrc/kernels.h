@@ -49,6 +49,19 @@ __device__ __forceinline__ int64_t kv_offset(const PageMap& pm, int64_t s_page, 
   return (int64_t)page_of(pm, prob, tok) * s_page + (int64_t)c * s_head + (tok & ((1 << pm.shift) - 1)) * s_token;
 }
 
+// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy of
+// the kernel).  `done`: one bit per device, file-scope state of the caller.  Two host threads racing
+// here at worst set the attribute twice.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, uint64_t* done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 64 && ((*done >> dev) & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev < 64) *done |= 1ull << dev;
+  return e;
+}
+
 // Rows a gated launch works on: row = row_map[blockIdx] while blockIdx < *n_active (both device
 // memory).  Null row_map = all rows, identity.
 struct RowGate {

@@ -423,16 +423,11 @@ hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s) {
   const int64_t E = p.geo.L - p.S - p.W;
   const size_t lds = (size_t)((E + 31) / 32) * 4;
   if (lds > 64 * 1024 || p.geo.G > kFastMaxG) return hipErrorInvalidValue;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)topk_cand_kernel<DT_BF16, false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)topk_cand_kernel<DT_BF16, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              64 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static uint64_t done_one = 0, done_pq = 0;
+  const hipError_t e = p.n_lists > 1
+                           ? allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16, true>, 64 * 1024, &done_pq)
+                           : allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16, false>, 64 * 1024, &done_one);
+  if (e != hipSuccess) return e;
   const dim3 grid((unsigned)(rows * p.n_lists));
   if (p.n_lists > 1)
     hipLaunchKernelGGL((topk_cand_kernel<DT_BF16, true>), grid, dim3(kTopkThreads), lds, s, p);

@@ -442,15 +442,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
 
 hipError_t launch_topk(const TopkParams& p0, hipStream_t s) {
   constexpr int kMaxBitmap = 64 * 1024;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)topk_kernel<DT_BF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kMaxBitmap);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)topk_kernel<DT_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBitmap);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static uint64_t done_bf16 = 0, done_f32 = 0;
+  hipError_t e = p0.geo.dtype == DT_BF16 ? allow_dynamic_lds((const void*)topk_kernel<DT_BF16>, kMaxBitmap, &done_bf16)
+                                         : allow_dynamic_lds((const void*)topk_kernel<DT_F32>, kMaxBitmap, &done_f32);
+  if (e != hipSuccess) return e;
   TopkParams p = p0;
   const int64_t E = p.geo.L - p.S - p.W;
   const int64_t need = ((E + 3 + 31) / 32 + 3) / 4 * 16;  // one bit per candidate, whatever the row's alignment
