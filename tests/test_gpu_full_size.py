@@ -157,7 +157,7 @@ def test_C4_per_query_paper_budget_full(ref):
 
 
 def test_C5_length_dense_path(ref):
-    """The dense path (every token's score written, multi-workgroup histograms, 4-pass top-k) at the
+    """The dense path (every token's score written, multi-workgroup histograms, bitmap top-k) at the
     longest configured row, L = 524288, on two layers; kept sets and scores against the oracle."""
     import torch
 
