@@ -116,6 +116,24 @@ def test_select_tiny_rows_at_every_alignment(ref):
                 select_parity(ref, F32, q, K, V, S, W, k)
 
 
+def test_select_ties_at_every_alignment(ref):
+    """q = 0 makes every score equal, so the dense top-k takes its general route (exact radix select,
+    count-then-write compaction by wave-owned segments) and must hand the ties to the lowest indices,
+    at every offset of the candidate range against its 16-byte loads and with ragged ends."""
+    for S in range(4):
+        for E in (5, 9, 300, 5003):
+            W = 3 + (S + E) % 2
+            L = S + E + W
+            q, K, V = rand_case(400 + 10 * S + E % 7, 1, 4, 2, 64, L, BF16)
+            q[:] = 0
+            for k in sorted({1, E // 2, E - 1}):
+                for want_scores in (True, False):
+                    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=want_scores)
+                    want = list(range(S + k)) + list(range(L - W, L))
+                    for c in range(2):
+                        assert out["kept"][0, c].tolist() == want, (S, E, k, want_scores)
+
+
 def test_select_row_longer_than_the_lds_bitmap(ref):
     """More than 512K candidates: the dense top-k writes its output with the two-pass route."""
     P, Hq, Hkv, d, L, S, W, k = 1, 2, 1, 64, 540001, 3, 50, 2000
