@@ -422,18 +422,30 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
   char* Vc = (char*)p.Vc + (int64_t)row * p.cap * row_bytes;
   const int32_t* kept = p.kept_idx + (int64_t)row * p.n_kept;
   const int t0 = blockIdx.x * kGatherTokens;
+  constexpr int NIT = kGatherTokens / TPI;
+  // all of a thread's loads are issued before its first store: positions first, then the rows
+  // (streaming loads: the full cache is not read again)
+  int64_t src[NIT];
 #pragma unroll
-  for (int it = 0; it < kGatherTokens / TPI; ++it) {
+  for (int it = 0; it < NIT; ++it) {
+    const int t = t0 + it * TPI + sub;
+    src[it] = kept[t < p.n_kept ? t : p.n_kept - 1];
+  }
+  uint4 a[NIT], b[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int64_t i = src[it] < 0 ? 0 : (src[it] >= p.geo.L ? p.geo.L - 1 : src[it]);  // never read outside the row
+    const int64_t ko = kv_offset(p.pm, p.pm.ks_page, p.ks_problem, p.ks_head, p.ks_token, prob, c, i);
+    const int64_t vo = kv_offset(p.pm, p.pm.vs_page, p.vs_problem, p.vs_head, p.vs_token, prob, c, i);
+    a[it] = ld16_stream((const char*)p.K + ko * eb + cl * 16);
+    b[it] = ld16_stream((const char*)p.V + vo * eb + cl * 16);
+  }
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
     const int t = t0 + it * TPI + sub;
     if (t < p.n_kept) {
-      int64_t src = kept[t];
-      src = src < 0 ? 0 : (src >= p.geo.L ? p.geo.L - 1 : src);  // never read outside the row
-      const int64_t ko = kv_offset(p.pm, p.pm.ks_page, p.ks_problem, p.ks_head, p.ks_token, prob, c, src);
-      const int64_t vo = kv_offset(p.pm, p.pm.vs_page, p.vs_problem, p.vs_head, p.vs_token, prob, c, src);
-      const uint4 a = ld16((const char*)p.K + ko * eb + cl * 16);
-      const uint4 b = ld16((const char*)p.V + vo * eb + cl * 16);
-      st16(Kc + t * row_bytes + cl * 16, a);
-      st16(Vc + t * row_bytes + cl * 16, b);
+      st16(Kc + t * row_bytes + cl * 16, a[it]);
+      st16(Vc + t * row_bytes + cl * 16, b[it]);
     }
   }
 }
