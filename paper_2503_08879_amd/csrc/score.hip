@@ -18,6 +18,7 @@ namespace {
 
 constexpr int kScoreThreads = 256;
 constexpr int kScoreWaves = kScoreThreads / kWave;
+constexpr int kGatedRowBlocks = 16;  // y-blocks of a gated score / combine launch
 constexpr int kBlocksPerWave = kScoreChunk / (kScoreWaves * 64);  // 64-token blocks per wave
 
 // Logit scratch layout: [row][chunk][head][kScoreChunk], so a score workgroup writes one
@@ -142,8 +143,9 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
 //
 // PAGED: the chunk's pages (at most 64: pages hold 16 tokens or more) are looked up once, one per
 // lane, and every load takes its page from the lane that holds it.
+// One score chunk (kScoreChunk tokens of row `row`) by one workgroup of kScoreThreads threads.
 template <int D, int GPAD, bool FILTER, bool PAGED>
-__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p, int gb) {
+__device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, int row, int chunk) {
   constexpr int CH = D / 8;         // 16-byte chunks per token
   constexpr int TPL = 64 / CH;      // tokens per coalesced wave load
   constexpr int NLOAD = 64 / TPL;   // loads per 64-token block
@@ -155,11 +157,6 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
   __shared__ float2 part[kScoreWaves][4][4];
   __shared__ int n_kept_wg;  // FILTER: candidates this workgroup has kept so far
 
-  int row = blockIdx.y;
-  if (p.gate.row_map) {
-    if ((int)blockIdx.y >= *p.gate.n_active) return;
-    row = p.gate.row_map[blockIdx.y];
-  }
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tq = lane / CH, cl = lane % CH;  // load role: token sub-index, chunk
@@ -172,7 +169,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
   int my_page = 0, first_page = 0;
   if (PAGED) {
     Krow = (const char*)p.K + (int64_t)c * p.ks_head * 2;
-    first_page = (int)(((int64_t)blockIdx.x * kScoreChunk) >> p.pm.shift);
+    first_page = (int)(((int64_t)chunk * kScoreChunk) >> p.pm.shift);
     const int last_page = (int)((L - 1) >> p.pm.shift);
     const int pg = first_page + lane < last_page ? first_page + lane : last_page;
     my_page = page_of(p.pm, prob, (int64_t)pg << p.pm.shift);
@@ -188,7 +185,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
 
   // The waves of a workgroup take the chunk's 64-token blocks round robin, so the workgroup reads
   // one contiguous 64 KiB run at a time; the first block's loads go out before anything else.
-  const int64_t wave_base = (int64_t)blockIdx.x * kScoreChunk + (int64_t)wave * 64;
+  const int64_t wave_base = (int64_t)chunk * kScoreChunk + (int64_t)wave * 64;
   constexpr int64_t kBlockStride = 64 * kScoreWaves;
   uint4 kv[NLOAD];
   if (wave_base < L) {
@@ -237,7 +234,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
     if (threadIdx.x == 0) n_kept_wg = 0;
     __syncthreads();
   }
-  const int64_t slot_base = ((int64_t)row * p.n_chunks + blockIdx.x) * kScoreChunk;  // FILTER: this chunk's slots
+  const int64_t slot_base = ((int64_t)row * p.n_chunks + chunk) * kScoreChunk;  // FILTER: this chunk's slots
 
   // Software pipeline: the loads of block b+1 are issued right after block b went to LDS, so
   // their latency overlaps block b's MFMA phase.  The logits stay in registers until the wave
@@ -353,7 +350,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
     if (n == 0) part[wave][j][r] = make_float2(M, s);
   }
   __syncthreads();
-  if (FILTER && threadIdx.x == 0) p.filt.cand_count[(int64_t)row * p.n_chunks + blockIdx.x] = n_kept_wg;
+  if (FILTER && threadIdx.x == 0) p.filt.cand_count[(int64_t)row * p.n_chunks + chunk] = n_kept_wg;
   if ((int)threadIdx.x < gb) {
     const int g = threadIdx.x;
     float M = -INFINITY;
@@ -367,8 +364,24 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p
           const float2 pw = part[w][jj][g % 4];
           s += (pw.x == -INFINITY) ? 0.f : pw.y * exp_fast(pw.x - M);
         }
-    p.partials[((int64_t)row * p.geo.G + p.g0 + g) * p.n_chunks + blockIdx.x] = make_float2(M, s);
+    p.partials[((int64_t)row * p.geo.G + p.g0 + g) * p.n_chunks + chunk] = make_float2(M, s);
   }
+}
+
+// grid (chunks, rows).  A gated launch (rows the pre-filter could not certify, usually none) has a
+// few y-blocks only, each looping over the active rows: an empty launch then costs a handful of
+// workgroups instead of one per (chunk, row).
+template <int D, int GPAD, bool FILTER, bool PAGED>
+__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p, int gb) {
+  if (!FILTER && p.gate.row_map) {
+    const int n_active = *p.gate.n_active;
+    for (int i = blockIdx.y; i < n_active; i += gridDim.y) {
+      score_mfma_chunk<D, GPAD, FILTER, PAGED>(p, gb, p.gate.row_map[i], (int)blockIdx.x);
+      __syncthreads();  // the chunk's last LDS reads, before the next row's writes
+    }
+    return;
+  }
+  score_mfma_chunk<D, GPAD, FILTER, PAGED>(p, gb, (int)blockIdx.y, (int)blockIdx.x);
 }
 
 // Logits of the sampled blocks (fast path), same MFMA scheme as score_mfma_kernel: one wave per
@@ -485,11 +498,11 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
   __shared__ int hist[kHistBins];
   __shared__ float sM[kMaxG], sInv[kMaxG];
   const int tid = threadIdx.x;
-  int row = blockIdx.y;
-  if (p.gate.row_map) {
-    if ((int)blockIdx.y >= *p.gate.n_active) return;
-    row = p.gate.row_map[blockIdx.y];
-  }
+  // a gated launch has a few y-blocks, each looping over the active rows (see score_mfma_kernel)
+  const bool gated = p.gate.row_map != nullptr;
+  const int n_active = gated ? *p.gate.n_active : 0;
+  for (int ry = blockIdx.y; !gated || ry < n_active; ry += gridDim.y) {
+  const int row = gated ? p.gate.row_map[ry] : ry;
 
   const int G = p.geo.G;
   const int64_t L = p.geo.L;
@@ -538,6 +551,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
   for (int b = tid; b < kHistBins; b += kCombineThreads) {
     int v = hist[b];
     if (v) atomicAdd(&gh[b], v);
+  }
+  if (!gated) break;
+  __syncthreads();  // hist and the statistics are rewritten for the next row
   }
 }
 
@@ -606,7 +622,9 @@ int max_group_per_launch() { return 8; }
 
 hipError_t launch_score(const ScoreParams& p0, hipStream_t s) {
   const int rows = p0.geo.n_problems * p0.geo.Hkv;
-  dim3 grid((unsigned)p0.n_chunks, (unsigned)rows);
+  // gated bf16 launches loop over the active rows in the kernel (the fp32 kernel has one y-block per row)
+  const bool few = p0.gate.row_map && p0.geo.dtype == DT_BF16;
+  dim3 grid((unsigned)p0.n_chunks, (unsigned)(few && rows > kGatedRowBlocks ? kGatedRowBlocks : rows));
   const int per_launch = p0.geo.dtype == DT_BF16 ? 16 : max_group_per_launch();
   for (int g0 = 0; g0 < p0.geo.G; g0 += per_launch) {
     ScoreParams p = p0;
@@ -630,7 +648,8 @@ hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s) {
 hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
   const int rows = p.geo.n_problems * p.geo.Hkv;
   const unsigned nx = (unsigned)((p.geo.L + kCombineChunk - 1) / kCombineChunk);
-  hipLaunchKernelGGL(combine_kernel, dim3(nx, (unsigned)rows, (unsigned)p.n_lists), dim3(kCombineThreads), 0, s, p);
+  const unsigned ny = (unsigned)(p.gate.row_map && rows > kGatedRowBlocks ? kGatedRowBlocks : rows);
+  hipLaunchKernelGGL(combine_kernel, dim3(nx, ny, (unsigned)p.n_lists), dim3(kCombineThreads), 0, s, p);
   return hipGetLastError();
 }
 

@@ -232,6 +232,21 @@ def test_prefilter_falls_back_when_all_scores_tie(ref):
         assert out["kept"][0, c].tolist() == want
 
 
+def test_prefilter_falls_back_for_more_rows_than_a_gated_launch_has_row_blocks(ref):
+    """20 rows that all tie: the gated dense stages loop over the flagged rows inside their workgroups."""
+    P, Hq, Hkv, d, L, S, W, k = 10, 8, 2, 64, 20000, 3, 40, 400
+    q, K, V = rand_case(12, P, Hq, Hkv, d, L, BF16)
+    q[:] = 0
+    q[7] = rand_case(13, 1, Hq, Hkv, d, 8, BF16)[0][0]   # one problem with ordinary scores in between
+    out, _ = select_parity(ref, BF16, q, K, V, S, W, k)
+    assert out["redone"] == (P - 1) * Hkv
+    want = list(range(S + k)) + list(range(L - W, L))
+    for pr in range(P):
+        if pr != 7:
+            for c in range(Hkv):
+                assert out["kept"][pr, c].tolist() == want
+
+
 @pytest.mark.parametrize("sampled", [True, False])
 def test_prefilter_with_one_token_carrying_most_of_the_mass(ref, sampled):
     """One candidate holds ~70% of head 0's attention.  Scaled up by the sampling rate it would make
