@@ -106,17 +106,29 @@ __device__ __forceinline__ int wave_sum_i(int v) {
   return v;
 }
 
-// exp(x) for x <= 0-ish via the hardware exp2, with the rounding error of x*log2(e) folded back in
-// (relative error a few 1e-7 down to x ~ -80).
-__device__ __forceinline__ float exp_accurate(float x) {
+// exp(x) * inv for x <= 0-ish and a normal `inv` in [2^-62, 1] (a softmax weight: inv = 1/Z), via the
+// hardware exp2 with the rounding error of x*log2(e) folded back in (relative error a few 1e-7 where
+// the result is a normal number).  The hardware exp2 returns 0 for every result under 2^-126, whereas
+// the product is wanted correctly rounded all the way down through the denormal range (scores are
+// RANKED, and fp32 keeps denormals): an argument more than 64 octaves down is raised by 64 octaves
+// before exp2 (exact: the sum has a finer ulp than the argument) and the factor is lowered by 2^-64
+// instead, so the final multiply rounds into the denormal range like any fp32 product.  Results
+// under 2^-190 * inv come out as 0, which is also their nearest fp32 value.
+__device__ __forceinline__ float exp_times(float x, float inv) {
   const float l2e_hi = 1.44269502162933349609375f;  // float(log2 e)
   const float l2e_lo = 1.92596299112661746e-8f;     // log2 e - l2e_hi
-  float t = x * l2e_hi;
+  const float t = x * l2e_hi;
   float e = fmaf(x, l2e_hi, -t);
   e = fmaf(x, l2e_lo, e);
-  float r = __builtin_amdgcn_exp2f(t);
-  return fmaf(r, e * 0.693147182464599609375f, r);
+  const bool far = t < -64.f;
+  float r = __builtin_amdgcn_exp2f(far ? t + 64.f : t);
+  r = fmaf(r, e * 0.693147182464599609375f, r);
+  return r * (far ? inv * 0x1p-64f : inv);
 }
+
+// Absolute slack that goes with the relative band around a coarse k-th score: below 2^-126 an fp32
+// score is a multiple of 2^-149, each head's term is rounded to that grid, and up to 64 heads add up.
+constexpr float kDenormSlack = 0x1p-142f;
 
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269502162933349609375f); }
 

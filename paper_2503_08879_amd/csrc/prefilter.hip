@@ -276,7 +276,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         float a = 0.f;
-        a += exp_accurate(x[u] - sM[gl]) * sInv[gl];
+        a += exp_times(x[u] - sM[gl], sInv[gl]);
         const bool keep = chunk_base[u] >= 0 && a >= bound;
         const unsigned long long bal = __ballot(keep);
         if (bal) {  // wave-uniform
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
             const float x[4] = {lg[u][g4].x, lg[u][g4].y, lg[u][g4].z, lg[u][g4].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (g4 * 4 + e < G) a += exp_accurate(x[e] - sM[g4 * 4 + e]) * sInv[g4 * 4 + e];
+              if (g4 * 4 + e < G) a += exp_times(x[e] - sM[g4 * 4 + e], sInv[g4 * 4 + e]);
           }
         cs[dj] = a;
         ci[dj] = ti[u];
@@ -334,13 +334,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   int quota;
   radix_select(sh, cs, n_c, k, false, &tau, &quota);
   const float tf = __uint_as_float(tau);
-  const float lo = tf * (1.0f - p.band), hi = tf * (1.0f + p.band);
+  const float lo = tf * (1.0f - p.band) - kDenormSlack, hi = tf * (1.0f + p.band) + kDenormSlack;
   // every token outside the list scores below bound[row]: the row is certified only if no such
   // token can reach the band
   if (!(lo * (1.0f - p.band) > p.bound[list])) {
-#ifdef SAGEKV_PROBE_FAILPRINT
-    if (tid == 0) printf("row %d list %d: k-th %g bound %g n_c %d n_all %d k %d\n", row, list, tf, p.bound[list], n_c, n_all, k);
-#endif
     if (tid == 0) p.row_fail[row] = 3;
     return;
   }
@@ -396,9 +393,6 @@ __global__ __launch_bounds__(kTopkThreads) void collect_failed_kernel(const int*
   for (int r0 = 0; r0 < rows; r0 += kTopkThreads) {
     const int r = r0 + threadIdx.x;
     const int f = r < rows ? (row_fail[r] != 0) : 0;
-#ifdef SAGEKV_PROBE_FAILPRINT
-    if (f) printf("row %d fails: reason %d\n", r, row_fail[r]);
-#endif
     int tot;
     const int incl = block_scan_incl<kTopkThreads>(f, wave_tot, &tot);
     if (f) fail_list[run + incl - 1] = r;

@@ -450,6 +450,7 @@ __global__ __launch_bounds__(kScoreThreads) void sample_logits_kernel(SamplePara
 }
 
 __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
+  constexpr double kFlushed = 0x1p-126;  // results of the hardware exp2 below this are 0
   const int lane = threadIdx.x;
   int row = blockIdx.x;
   if (p.gate.row_map) {
@@ -459,6 +460,7 @@ __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
   if (p.ghist)
     for (int b = lane; b < kHistBins * p.n_lists; b += 64) p.ghist[(int64_t)row * p.n_lists * kHistBins + b] = 0;
   double rho = 0.0;  // max over heads of (exact softmax weight) / (sampled softmax weight)
+  double flushed = 0.0;  // what the filter's approximate score can miss, see below
   for (int g = 0; g < p.G; ++g) {
     const float2* pr = p.partials + ((int64_t)row * p.G + g) * p.n_chunks;
     float M = -INFINITY;
@@ -481,14 +483,19 @@ __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
         const float2 ss = p.samp_stats[(int64_t)row * p.G + g];
         const double r = exp((double)ss.x - (double)M) / (z * (double)ss.y);
         rho = r > rho || !(r == r) ? r : rho;
+        flushed += kFlushed * (double)ss.y;
         if (p.n_lists > 1)  // per-query lists: head g's own bound
-          p.bound[(int64_t)row * p.n_lists + g] = (float)(r * (double)p.samp_tau[(int64_t)row * p.n_lists + g] * 1.001);
+          p.bound[(int64_t)row * p.n_lists + g] =
+              (float)(r * ((double)p.samp_tau[(int64_t)row * p.n_lists + g] + kFlushed * (double)ss.y) * 1.001);
       }
     }
   }
   // A token the filter dropped had approximate score < tau^; its exact score is below rho * tau^
-  // (plus fp32 slack).  The candidate selection checks its threshold against this bound.
-  if (p.bound && p.n_lists == 1 && lane == 0) p.bound[row] = (float)(rho * (double)p.samp_tau[row] * 1.001);
+  // (plus fp32 slack).  The candidate selection checks its threshold against this bound.  The
+  // filter's exponentials come out as 0 below 2^-126 (hardware exp2), so a dropped token's true
+  // approximate score may exceed the computed one by up to 2^-126 / Z^ per head.
+  if (p.bound && p.n_lists == 1 && lane == 0)
+    p.bound[row] = (float)(rho * ((double)p.samp_tau[row] + flushed) * 1.001);
 }
 
 constexpr int kCombineThreads = 256;
@@ -528,10 +535,10 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     for (int g = g_lo; g < g_hi; ++g) {
       const float4 x = *reinterpret_cast<const float4*>(p.logits + logit_index(p.geo, p.n_chunks, row, g, tok));
       const float M = sM[g], inv = sInv[g];
-      acc[0] += exp_accurate(x.x - M) * inv;
-      acc[1] += exp_accurate(x.y - M) * inv;
-      acc[2] += exp_accurate(x.z - M) * inv;
-      acc[3] += exp_accurate(x.w - M) * inv;
+      acc[0] += exp_times(x.x - M, inv);
+      acc[1] += exp_times(x.y - M, inv);
+      acc[2] += exp_times(x.z - M, inv);
+      acc[3] += exp_times(x.w - M, inv);
     }
     if (vec_out && tok + 3 < L) {
       *reinterpret_cast<float4*>(out + tok) = make_float4(acc[0], acc[1], acc[2], acc[3]);

@@ -156,7 +156,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   //    (then no score outside the band can compare differently).  Anything else (a huge band of
   //    near-ties, a refined value on the band's edge) takes the general route: patch, then a full
   //    radix select of the patched row.
-  const float lo = __uint_as_float(tau) * (1.0f - p.band), hi = __uint_as_float(tau | 0x1FFu) * (1.0f + p.band);
+  // (below 2^-126 the scores sit on the 2^-149 grid: the band is at least kDenormSlack wide each way)
+  const float lo = __uint_as_float(tau) * (1.0f - p.band) - kDenormSlack,
+              hi = __uint_as_float(tau | 0x1FFu) * (1.0f + p.band) + kDenormSlack;
   __shared__ int band_i[kDenseBand];
   __shared__ float band_v[kDenseBand];
   __shared__ int n_band, n_above, short_ok;

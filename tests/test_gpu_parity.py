@@ -317,6 +317,69 @@ def test_prefilter_certifies_model_like_attention(ref):
         np.testing.assert_array_equal(out["Vc"], Vc)
 
 
+def far_down_case(seed, P, Hq, Hkv, d, L, scale):
+    """Queries scaled so that the logits have a standard deviation of about `scale`."""
+    q, K, V = rand_case(seed, P, Hq, Hkv, d, L, BF16)
+    return synth.round_to_dtype(scale * synth.to_f64(q, BF16), BF16), K, V
+
+
+def check_far_down(ref, head_mode, q, K, V, S, W, k, route, min_far):
+    """Kept sets and gathered rows against the oracle where the k-th score lies under fp32's normal
+    range (2^-126): the oracle ranks the fp32-rounded scores, denormals included, and exact zeros by
+    index.  route: 'scores' (dense, scores_out given), 'dense' (flag) or 'auto' (pre-filtered where it applies)."""
+    P, Hq, d = q.shape
+    Hkv, L = K.shape[1], K.shape[2]
+    G = Hq // Hkv if head_mode == 1 else 1
+    Kc, Vc, kept, s = ref.select(BF16, head_mode, q, K, V, S, W, k, want_scores=True)  # s [P,Hkv,lists,L]
+    tiny = np.float32(2.0 ** -126)
+    cand = s[..., S:L - W]
+    kth = np.sort(cand, axis=-1)[..., ::-1][..., k - 1]
+    assert (kth < tiny).mean() >= min_far, f"only {(kth < tiny).mean():.2f} of the lists have a k-th score under 2^-126"
+    assert ((cand < tiny) & (cand > 0)).any(), "no denormal score in the case"
+    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=route == "scores", flags=1 if route == "dense" else 0,
+                        head_mode=head_mode)
+    if route == "scores":
+        # fp32 logits carry an absolute error that grows with their size (~|logit| 2^-24 times a few), so do
+        # the scores relative to their size; below 2^-126 they sit on the 2^-149 grid, each head's term rounded to it
+        g, w = out["scores"].reshape(s.shape).astype(np.float64), s.astype(np.float64)
+        assert np.all(np.abs(g - w) <= 1e-3 * w + (Hq // Hkv + 1) * 2.0 ** -149)
+    for li in range(G):
+        cut = lambda a: np.concatenate([a[..., :S], a[..., S + li * k:S + (li + 1) * k], a[..., S + G * k:]], axis=-1)
+        got, want = cut(out["kept"]), cut(kept)
+        if not np.array_equal(got, want):
+            assert (kth[:, :, li] > 0).all(), "kept sets differ where the k-th score is an exact zero (ties go by index)"
+            gu.check_kept(got, want, s[:, :, li], S, W, k)
+    if np.array_equal(out["kept"], kept):
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
+    return out
+
+
+@pytest.mark.parametrize("head_mode", [0, 1])
+@pytest.mark.parametrize("route", ["scores", "dense"])
+@pytest.mark.parametrize("k_kind", ["E/8", "E/4", "E/2", "E-1"])
+def test_select_ranks_scores_below_the_normal_range_dense(ref, head_mode, route, k_kind):
+    """Logits spread over +-150: most candidates sit more than 100 logits below their row maximum,
+    where exp() leaves fp32's normal range.  The selection must still follow the oracle: denormal
+    scores by value, exact zeros by index."""
+    P, Hq, Hkv, d, L, S, W = 2, 8, 2, 128, 5200, 4, 40
+    E = L - S - W
+    k = {"E/8": E // 8, "E/4": E // 4, "E/2": E // 2, "E-1": E - 1}[k_kind]
+    q, K, V = far_down_case(500, P, Hq, Hkv, d, L, 40.0)
+    check_far_down(ref, head_mode, q, K, V, S, W, k, route, min_far=1.0 if k_kind in ("E/2", "E-1") else 0.0)
+
+
+@pytest.mark.parametrize("head_mode", [0, 1])
+@pytest.mark.parametrize("scale,k", [(40.0, 2500), (50.0, 3000), (55.0, 4000), (70.0, 2000)])
+def test_select_ranks_scores_below_the_normal_range_prefiltered(ref, head_mode, scale, k):
+    """The same regime on a row long enough for the pre-filtered path (5 k lists <= E): whether it can
+    certify such a row or hands it to the dense path, the kept set is the oracle's."""
+    P, Hq, Hkv, d, L, S, W = 1, 4, 2, 128, 60000, 4, 64
+    q, K, V = far_down_case(501, P, Hq, Hkv, d, L, scale)
+    out = check_far_down(ref, head_mode, q, K, V, S, W, k, "auto", min_far=0.5 if scale > 50 else 0.0)
+    assert out["redone"] >= 0  # the call went through the pre-filtered path
+
+
 def test_select_C2_shape_two_layers(ref):
     """Config C2's row shape (32q/8kv, d128, bf16, L 32768, 4+1788+256) on 2 of its 32 layers."""
     cfg = synth.CONFIGS["C2"].with_(n_layers=2)
