@@ -10,8 +10,8 @@
  *   - Every data pointer is DEVICE memory owned by the caller (unless a comment
  *     says host).  Descriptors are host structs, read during the call only.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, null =
- *     the default stream).  No call allocates, frees or synchronises (the two benchmark aids
- *     that wait for the stream say so).
+ *     the default stream).  No call allocates, frees or synchronises (the benchmark aids of
+ *     sagekv_bench.h that wait for the stream say so).
  *   - Indices are 0-based.  A "problem" is one layer of one sequence; problems are
  *     independent (Sec. 2: selection is done "for each layer").  A "row" is one
  *     (problem, KV head).  G = n_q_heads / n_kv_heads consecutive query heads share
@@ -130,11 +130,21 @@ sagekv_status sagekv_select_paged(const sagekv_select_desc* desc, const sagekv_p
                                   const void* K_pool, const void* V_pool, void* Kc, void* Vc, int32_t* kept_idx,
                                   float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Test / benchmark aid: waits for the stream, then reports how many rows of the LAST sagekv_select
- * call that used this workspace were redone by the dense path (-1 if the call was dense anyway).
- * `n_rows` is a host pointer. */
-sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* desc, const void* workspace,
-                                        size_t workspace_bytes, void* hip_stream, int32_t* n_rows);
+/* Interval refresh (Sec. 4, future work: "the model periodically refreshes the selected tokens
+ * during generation").  The library keeps no state between calls, so a refresh is a second
+ * sagekv_select with the CURRENT token's query over the full cache as it stands now.  Contract:
+ *   - the caller keeps the full cache (K, V with spare capacity behind L; the stride fields address
+ *     it) and stores every generated token's (k, v) at positions L0, L0+1, ... itself: decode calls
+ *     only write the reduced cache;
+ *   - after T generated tokens, call sagekv_select with L = L0 + T, the query of the newest token
+ *     (the one at position L - 1) and the SAME Kc, Vc, kept_idx as before: rows [0, S+lists*k+W) of
+ *     every reduced row and of kept_idx are rewritten in full, on the stream, after the decode
+ *     steps already enqueued there;
+ *   - the recent window is then again positions [L - W, L) in ascending order in slots
+ *     [S+lists*k, S+lists*k+W): restart the append count (n_appended = 0 for the next
+ *     sagekv_decode_step; with sagekv_decode_step_ring set ring_state[0] = ring_state[1] = 0 on the
+ *     stream);
+ *   - a grown row (grow_recent) starts again at length S+lists*k+W. */
 
 /* ---- decoding over the reduced cache -------------------------------------------------- */
 typedef struct {
@@ -175,6 +185,19 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* desc, const void* q, 
                                  const void* v_new, void* Kc, void* Vc, int32_t n_appended, float* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* sagekv_decode_step with the append count kept ON THE DEVICE (Step 4's FIFO position), so that one
+ * recorded launch sequence (a HIP graph of a decode step) serves every generated token.
+ * ring_state: device int32[2], owned by the caller.  ring_state[0] = tokens appended so far, read by
+ * the launch in place of `n_appended` and increased by one when the step is done; ring_state[1] is
+ * the library's arrival counter (it is 0 between calls).  Set both to 0 before the first step and
+ * after every sagekv_select into this reduced cache (stream-ordered, e.g. a fill kernel: a memset
+ * node must not be recorded into a graph).  Calls on one ring_state must not overlap.
+ * grow_recent: a row that has reached compact_capacity stays as it is (the token is dropped and the
+ * count still moves on); the caller sizes compact_capacity for the tokens it will generate. */
+sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* desc, const void* q, const void* k_new,
+                                      const void* v_new, void* Kc, void* Vc, int32_t* ring_state, float* out,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Window-relative rotary positions (the StreamLLM_R cache mode of Sec. 3.1, baseline (3a), App. A.1:
  * the entry at index i of a window of n entries has position i, the query position n-1, so
  * positions stay bounded however long the generation runs).  Rotary attention depends on position
@@ -205,23 +228,6 @@ const char* sagekv_status_string(sagekv_status s); /* host string, static storag
  * heads per KV head.  INVALID_ARG (outputs untouched) for null outputs, G < 1 or B < 4*G (no room
  * for one token per head). */
 sagekv_status sagekv_paper_budget(int32_t B, int32_t G, int32_t* n_sink, int32_t* k, int32_t* n_recent);
-
-/* Stage timing for benchmarks (host-side state, per process; not thread safe).
- * sagekv_stage_timing_enable(n) creates HIP events for the next n instrumented calls of
- * sagekv_select and n of sagekv_decode_attn / sagekv_decode_step (n = 0 switches it off and
- * destroys the events).  While enabled, each call records an event pair around every stage's
- * launches on the call's own stream.  sagekv_stage_timing_read(which, call, ms) waits for that
- * call's events and returns the elapsed milliseconds per stage: which = 0 reads a select call
- * (ms[0 .. SAGEKV_N_STAGES), 0 for a stage the call did not run), which = 1 a decode call (ms[0] only). */
-enum { SAGEKV_STAGE_SAMPLE = 0, SAGEKV_STAGE_SCORE = 1, SAGEKV_STAGE_STATS = 2, SAGEKV_STAGE_COMBINE = 3,
-       SAGEKV_STAGE_TOPK = 4, SAGEKV_STAGE_REDO = 5, SAGEKV_STAGE_GATHER = 6, SAGEKV_N_STAGES = 7 };
-sagekv_status sagekv_stage_timing_enable(int32_t n_calls);
-sagekv_status sagekv_stage_timing_read(int32_t which, int32_t call, float* ms /* host */);
-/* Every event record leaves the GPU idle for some microseconds between two kernels (measured ~10 us
- * on MI355X), so a fully instrumented eviction pass is ~3 % slower than a plain one.  This restricts
- * the stages of sagekv_select that are bracketed (bit i = stage i; default: all) and says whether
- * decode calls are (decode != 0; default: yes).  Takes effect for the calls that follow. */
-sagekv_status sagekv_stage_timing_stages(uint32_t select_stage_mask, int32_t decode);
 
 #ifdef __cplusplus
 }

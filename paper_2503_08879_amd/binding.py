@@ -21,7 +21,7 @@ EXPORTS = (
     "sagekv_status_string", "sagekv_select_workspace_bytes", "sagekv_select", "sagekv_select_paged",
     "sagekv_select_redone_rows",
     "sagekv_append",
-    "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step",
+    "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step", "sagekv_decode_step_ring",
     "sagekv_decode_attn_window", "sagekv_decode_step_window",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read", "sagekv_stage_timing_stages",
     "sagekv_paper_budget",
@@ -94,6 +94,8 @@ def lib():
         L.sagekv_decode_attn.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step.restype = ctypes.c_int
         L.sagekv_decode_step.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.sagekv_decode_step_ring.restype = ctypes.c_int
+        L.sagekv_decode_step_ring.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.sagekv_decode_attn_window.restype = ctypes.c_int
         L.sagekv_decode_attn_window.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step_window.restype = ctypes.c_int
@@ -235,7 +237,13 @@ def sagekv_decode_step(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, n_appended: in
            "sagekv_decode_step")
 
 
-# ---------------------------------------------------------------------------------------- timing
+def sagekv_decode_step_ring(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, ring_state, out, workspace) -> None:
+    """sagekv_decode_step with the append count in ring_state (device int32[2], zeroed by the caller)."""
+    _check(lib().sagekv_decode_step_ring(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(Kc), _ptr(Vc),
+                                         _ptr(ring_state), _ptr(out), _ptr(workspace), _ws_bytes(workspace),
+                                         _stream()), "sagekv_decode_step_ring")
+
+
 def sagekv_decode_attn_window(desc: DecodeDesc, q, q_sink, Kc, Vc, length: int, out, workspace) -> None:
     _check(lib().sagekv_decode_attn_window(ctypes.byref(desc), _ptr(q), _ptr(q_sink), _ptr(Kc), _ptr(Vc), length,
                                            _ptr(out), _ptr(workspace), _ws_bytes(workspace), _stream()),
@@ -249,6 +257,7 @@ def sagekv_decode_step_window(desc: DecodeDesc, q, q_sink, k_new, v_new, Kc, Vc,
                                            _ws_bytes(workspace), _stream()), "sagekv_decode_step_window")
 
 
+# ---------------------------------------------------------------------------------------- measurement aids
 def sagekv_stage_timing_enable(n_calls: int) -> None:
     _check(lib().sagekv_stage_timing_enable(n_calls), "sagekv_stage_timing_enable")
 

@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsagekv.so")
 SOURCES = ["api.hip", "score.hip", "select.hip", "prefilter.hip", "decode.hip"]
-HEADERS = ["device_utils.h", "kernels.h", "radix_select.h", os.path.join("..", "..", "include", "sagekv.h")]
+HEADERS = ["device_utils.h", "kernels.h", "radix_select.h", os.path.join("..", "..", "include", "sagekv.h"),
+           os.path.join("..", "..", "include", "sagekv_bench.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 

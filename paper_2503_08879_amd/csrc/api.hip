@@ -1,9 +1,11 @@
 // C ABI of the library: argument checks, workspace layout, launch order.
 #include "../../include/sagekv.h"
+#include "../../include/sagekv_bench.h"
 
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "kernels.h"
@@ -182,9 +184,9 @@ struct DecodeLayout {
   int max_splits, rows, G;
 };
 
-// Splits per row.  With about one row per CU or more, a single 16-wave workgroup per row fills
+// Splits per row.  With about one row per CU or more, a single 8-wave workgroup per row fills
 // the chip and needs no merge launch; otherwise enough workgroups to fill 256 CUs several times
-// over, at least 256 tokens each.
+// over, at least 128 tokens each.
 int splits_for(int rows, int len) {
   if (rows >= 192) return 1;
   int want = (2048 + rows - 1) / rows;
@@ -248,16 +250,18 @@ sagekv_status dev(hipError_t e) { return e == hipSuccess ? SAGEKV_OK : SAGEKV_ER
 // Every cache and query row is read and written 16 bytes per lane.
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// `ring` (nullable, device): the count of appended tokens lives on the device; slot and len are then
+// derived in the kernels and the launch moves the count on.
 sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void* q_sink, const void* k_new,
                          const void* v_new,
-                         void* Kc, void* Vc, int slot, int len, float* out, void* ws, size_t ws_bytes,
+                         void* Kc, void* Vc, int slot, int len, int32_t* ring, float* out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
   if (!aligned16(q) || !aligned16(q_sink) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(Kc) ||
-      !aligned16(Vc) || ((uintptr_t)out & 3u) || !aligned16(ws))
+      !aligned16(Vc) || ((uintptr_t)out & 3u) || !aligned16(ws) || ((uintptr_t)ring & 3u))
     return SAGEKV_ERR_UNSUPPORTED;
   const DecodeLayout l = decode_layout(d);
   if (l.total > 0 && (!ws || ws_bytes < l.total)) return SAGEKV_ERR_WORKSPACE;
-  DecodeParams p;
+  DecodeParams p = {};
   p.n_problems = d->n_problems;
   p.Hq = d->n_q_heads;
   p.Hkv = d->n_kv_heads;
@@ -274,10 +278,16 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
   p.slot = slot;
   p.len = len;
   p.cap = d->compact_capacity;
-  p.n_splits = splits_for(l.rows, len);
+  // with the count on the device the length of a growing row is not known here: as many slices as
+  // the full capacity would take (a fixed-size window has its one length either way)
+  p.n_splits = splits_for(l.rows, ring && d->grow_recent ? d->compact_capacity : len);
   if (p.n_splits > l.max_splits) p.n_splits = l.max_splits;
-  const int tps = (len + p.n_splits - 1) / p.n_splits;
-  p.tokens_per_split = (tps + 63) / 64 * 64;
+  p.tokens_per_split = split_tokens(len, p.n_splits);
+  p.ring = ring;
+  p.ring_base = d->n_sink + decode_lists(d) * d->k;
+  p.ring_W = d->n_recent;
+  p.ring_grow = d->grow_recent;
+  p.ring_advance = ring != nullptr;
   // a reduced cache that cannot stay in L2 / Infinity Cache between steps is streamed (measured: +8 %)
   p.pq_S = d->n_sink;
   p.pq_k = decode_lists(d) > 1 ? d->k : 0;
@@ -661,7 +671,7 @@ sagekv_status sagekv_decode_attn(const sagekv_decode_desc* d, const void* q, con
   sagekv_status st;
   if (!check_decode(d, &st)) return st;
   if (!q || !Kc || !Vc || !out || len < 1 || len > d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
-  return run_decode(d, q, nullptr, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, out,
+  return run_decode(d, q, nullptr, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, nullptr, out,
                     workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
@@ -671,7 +681,7 @@ sagekv_status sagekv_decode_attn_window(const sagekv_decode_desc* d, const void*
   sagekv_status st;
   if (!check_decode(d, &st)) return st;
   if (!q || !q_sink || !Kc || !Vc || !out || len < 1 || len > d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
-  return run_decode(d, q, q_sink, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, out,
+  return run_decode(d, q, q_sink, nullptr, nullptr, const_cast<void*>(Kc), const_cast<void*>(Vc), -1, len, nullptr, out,
                     workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
@@ -685,7 +695,20 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* d, const void* q, con
   const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
   const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
-  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, (int)slot, (int)len, out, workspace, workspace_bytes,
+  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, (int)slot, (int)len, nullptr, out, workspace, workspace_bytes,
+                    (hipStream_t)hip_stream);
+}
+
+sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* d, const void* q, const void* k_new, const void* v_new,
+                                      void* Kc, void* Vc, int32_t* ring_state, float* out, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_decode(d, &st)) return st;
+  if (!q || !k_new || !v_new || !Kc || !Vc || !out || !ring_state) return SAGEKV_ERR_INVALID_ARG;
+  const int base = d->n_sink + decode_lists(d) * d->k;
+  // the longest row this step can attend (a growing row's length is only known on the device)
+  const int len = d->grow_recent ? d->compact_capacity : base + d->n_recent;
+  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, 0, len, ring_state, out, workspace, workspace_bytes,
                     (hipStream_t)hip_stream);
 }
 
@@ -699,7 +722,7 @@ sagekv_status sagekv_decode_step_window(const sagekv_decode_desc* d, const void*
   const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
   const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
-  return run_decode(d, q, q_sink, k_new, v_new, Kc, Vc, (int)slot, (int)len, out, workspace, workspace_bytes,
+  return run_decode(d, q, q_sink, k_new, v_new, Kc, Vc, (int)slot, (int)len, nullptr, out, workspace, workspace_bytes,
                     (hipStream_t)hip_stream);
 }
 

@@ -4,8 +4,8 @@
 // decode_kernel: grid (splits, rows).  A workgroup streams its slice of Kc and Vc once for all
 // G heads of the row (16-byte loads, LPT lanes per token), keeps an online softmax per lane
 // group and merges lane groups -> waves -> workgroup.  With one split per row (many rows: all
-// layers of a step in one launch) a 16-wave workgroup owns the whole row and writes `out`
-// itself; with few rows the row is split, partials (max, sum, acc[G][d]) go to scratch and
+// layers of a step in one launch) one workgroup (8 waves bf16, up to 16 fp32) owns the whole row and
+// writes `out` itself; with few rows the row is split, partials (max, sum, acc[G][d]) go to scratch and
 // combine_kernel merges them.  (A last-workgroup-done merge inside one kernel needs a device
 // scope fence in every workgroup, which on this multi-XCD part writes back and invalidates
 // L2: measured ~8x slower than two launches.)  The appended token is read from k_new / v_new
@@ -17,6 +17,37 @@
 namespace sagekv {
 
 namespace {
+
+// Slot of the new token, attended length and slice size of this launch: the host's values, or
+// derived from the device-side count of appended tokens.
+struct StepGeom {
+  int slot, len, tokens_per_split, n_appended;
+};
+__device__ __forceinline__ StepGeom step_geom(const DecodeParams& p) {
+  StepGeom s = {p.k_new ? p.slot : -1, p.len, p.tokens_per_split, 0};
+  if (p.ring) {
+    s.n_appended = p.ring[0];
+    const RingPos r = ring_position(p.ring_base, p.ring_W, p.ring_grow, p.cap, s.n_appended < 0 ? 0 : s.n_appended);
+    s.slot = p.k_new ? r.slot : -1;
+    s.len = r.len;
+    s.tokens_per_split = split_tokens(r.len, p.n_splits);
+  }
+  return s;
+}
+
+// Rows written by one workgroup each: the last workgroup of the launch to get here advances the
+// device-side count.  Every workgroup has read ring[0] before it takes its ticket (the value went
+// into its addresses), so the store cannot overtake a reader; the next launch on the stream sees
+// it.  Only the counter itself is exchanged between workgroups: relaxed atomics, no cache-wide fence.
+__device__ __forceinline__ void ring_arrive(const DecodeParams& p, const StepGeom& sg) {
+  if (!p.ring || !p.ring_advance || p.n_splits != 1 || threadIdx.x != 0) return;
+  const int total = (int)(gridDim.x * gridDim.y);
+  const int ticket = __hip_atomic_fetch_add(&p.ring[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (ticket == total - 1) {
+    __hip_atomic_store(&p.ring[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&p.ring[0], sg.n_appended + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 
 template <int DT, int D, int GB, int NW>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0) {
@@ -40,10 +71,11 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
   char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
-  const int slot = kn ? p.slot : -1;
+  const StepGeom sg = step_geom(p);
+  const int slot = sg.slot;
 
-  const int t_begin = split * p.tokens_per_split;
-  const int t_end = min(p.len, t_begin + p.tokens_per_split);
+  const int t_begin = split * sg.tokens_per_split;
+  const int t_end = min(sg.len, t_begin + sg.tokens_per_split);
 
   if (slot >= t_begin && slot < t_end && tid < LPT) {  // Step 4: the new token enters the window
     st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
@@ -167,6 +199,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
       if (j == 0) pml[g] = make_float2(M, ls);
     }
   }
+  ring_arrive(p, sg);
 }
 
 // bf16 decode with the q.K products on the matrix cores.  Per 32-token block a wave stages K
@@ -201,9 +234,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
-  const int slot = kn ? p.slot : -1;
-  const int t_begin = split * p.tokens_per_split;
-  const int t_end = min(p.len, t_begin + p.tokens_per_split);
+  const StepGeom sg = step_geom(p);
+  const int slot = sg.slot;
+  const int t_begin = split * sg.tokens_per_split;
+  const int t_end = min(sg.len, t_begin + sg.tokens_per_split);
   if (slot >= t_begin && slot < t_end && tid < CH) {  // Step 4: the new token enters the window
     st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
     st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
@@ -394,6 +428,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
       if (jj == 0) pml[g] = make_float2(M, ls);
     }
   }
+  ring_arrive(p, sg);
 }
 
 // bf16 decode with BOTH products on the matrix cores.  q.K as in decode_mfma_kernel.  The softmax
@@ -436,9 +471,10 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
-  const int slot = kn ? p.slot : -1;
-  const int t_begin = split * p.tokens_per_split;
-  const int t_end = min(p.len, t_begin + p.tokens_per_split);
+  const StepGeom sg = step_geom(p);
+  const int slot = sg.slot;
+  const int t_begin = split * sg.tokens_per_split;
+  const int t_end = min(sg.len, t_begin + sg.tokens_per_split);
   if (slot >= t_begin && slot < t_end && tid < CH) {  // Step 4: the new token enters the window
     st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
     st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
@@ -628,6 +664,7 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
       if (jj == 0) pml[g] = make_float2(M, ls);
     }
   }
+  ring_arrive(p, sg);
 }
 
 // Merges the splits of a row: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
@@ -635,6 +672,8 @@ __global__ __launch_bounds__(128) void combine_kernel(DecodeParams p) {
   const int row = blockIdx.x, g = blockIdx.y, j = threadIdx.x;  // one thread per output element
   const int prob = row / p.Hkv, c = row % p.Hkv;
   const int D = p.D;
+  // every slice kernel of the step has finished: the device-side count of appended tokens moves on
+  if (p.ring && p.ring_advance && row == 0 && g == 0 && j == 0) p.ring[0] = p.ring[0] + 1;
   if (j >= D) return;
   const float2* ml = p.part_ml + (int64_t)row * p.n_splits * p.G + g;
   const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g) * D + j;
@@ -745,6 +784,7 @@ hipError_t launch_decode(const DecodeParams& p, hipStream_t s) {
     const int gb = p.G - g0 < per_launch ? p.G - g0 : per_launch;
     DecodeParams q = p;
     if (g0 > 0) q.k_new = nullptr;  // the first launch already stored the new token
+    if (g0 + per_launch < p.G) q.ring_advance = 0;  // the last launch of the step moves the ring on
     hipError_t e;
     if (p.dtype == DT_BF16)
       e = p.D == 128 ? launch_decode_mfma<128>(q, g0, gb, grid, s) : launch_decode_mfma<64>(q, g0, gb, grid, s);

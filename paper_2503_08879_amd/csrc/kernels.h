@@ -226,6 +226,12 @@ struct DecodeParams {
   int slot;            // row position the new token takes, -1 = no append
   int len, cap;
   int n_splits, tokens_per_split;
+  // Device-side ring state (nullable).  ring[0] = tokens appended so far, ring[1] = arrival ticket of
+  // the launch that advances it.  When set, slot / len / tokens_per_split above are ignored and
+  // derived from ring[0] in the kernels (see ring_position); with ring_advance the last workgroup
+  // to finish (single-launch rows) or the merge kernel (split rows) stores ring[0] + 1.
+  int* ring;
+  int ring_base, ring_W, ring_grow, ring_advance;
   int stream_loads;    // reduced cache larger than the on-chip caches: read it with streaming loads
   // per-query head mode: rows are [sink | list of head 0 | ... | list of head G-1 | recent]; head g
   // attends the sink, its own list and the recent window.  pq_k = 0: every head attends everything.
@@ -249,6 +255,33 @@ hipError_t launch_gather(const GatherParams& p, hipStream_t s);
 hipError_t launch_decode(const DecodeParams& p, hipStream_t s);
 hipError_t launch_append(const DecodeParams& p, hipStream_t s);
 hipError_t launch_fill_u32(void* ptr, size_t n_words, uint32_t value, hipStream_t s);
+
+// Where the new token goes and how many tokens are attended, from the count n of tokens appended
+// before this step (paper Sec. 2 Step 4: the recent window is a FIFO of W entries, kept as a ring at
+// [base, base + W); grow mode keeps everything, rows [base + W, ...)).  A grown row that is full
+// keeps its length: the token is then not stored (slot = -1) and not attended.
+struct RingPos {
+  int slot, len;
+};
+__host__ __device__ inline RingPos ring_position(int base, int W, int grow, int cap, int n) {
+  RingPos r;
+  if (!grow) {
+    r.slot = base + n % W;
+    r.len = base + W;
+  } else if (base + W + n < cap) {
+    r.slot = base + W + n;
+    r.len = r.slot + 1;
+  } else {
+    r.slot = -1;
+    r.len = cap;
+  }
+  return r;
+}
+
+// Tokens per split of a row of `len` tokens cut into n_splits slices of whole 64-token blocks.
+__host__ __device__ inline int split_tokens(int len, int n_splits) {
+  return ((len + n_splits - 1) / n_splits + 63) / 64 * 64;
+}
 
 // Does query head g (index inside its group of G) attend position tok of a reduced row?
 __host__ __device__ inline bool head_attends(int pq_S, int pq_k, int G, int g, int tok) {
