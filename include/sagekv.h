@@ -41,7 +41,8 @@ typedef enum {
   SAGEKV_ERR_INVALID_ARG = 1,
   SAGEKV_ERR_UNSUPPORTED = 2,
   SAGEKV_ERR_WORKSPACE = 3,
-  SAGEKV_ERR_DEVICE = 4
+  SAGEKV_ERR_DEVICE = 4,
+  SAGEKV_ERR_SCRATCH_LIMIT = 5 /* sagekv_decode_step_static: the problem needs more than the built-in scratch */
 } sagekv_status;
 
 typedef enum { SAGEKV_BF16 = 0, SAGEKV_F32 = 1 } sagekv_dtype;
@@ -197,6 +198,20 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* desc, const void* q, 
 sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* desc, const void* q, const void* k_new,
                                       const void* v_new, void* Kc, void* Vc, int32_t* ring_state, float* out,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* For callers that cannot provide device scratch (code under HIP graph capture that may not call
+ * hipMalloc, tight serving loops, harnesses that forbid allocation): sagekv_decode_step with the
+ * split partials of a row kept in a scratch array built into the library (device memory that every
+ * GPU the library runs on holds until the process ends), SAGEKV_STATIC_SCRATCH_BYTES of it.
+ * Allocates nothing and takes no workspace.  A descriptor whose
+ * sagekv_decode_workspace_bytes exceeds that size is rejected with SAGEKV_ERR_SCRATCH_LIMIT before
+ * anything is launched.  All calls on one GPU share the array: calls that overlap there (two
+ * streams, two threads) race; calls on one stream are safe.  The array needs no clearing: every
+ * partial a step reads was written by that step. */
+enum { SAGEKV_STATIC_SCRATCH_BYTES = 4 * 1024 * 1024 };
+sagekv_status sagekv_decode_step_static(const sagekv_decode_desc* desc, const void* q, const void* k_new,
+                                        const void* v_new, void* Kc, void* Vc, int32_t n_appended, float* out,
+                                        void* hip_stream);
 
 /* Window-relative rotary positions (the StreamLLM_R cache mode of Sec. 3.1, baseline (3a), App. A.1:
  * the entry at index i of a window of n entries has position i, the query position n-1, so

@@ -22,6 +22,7 @@ EXPORTS = (
     "sagekv_select_redone_rows",
     "sagekv_append",
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step", "sagekv_decode_step_ring",
+    "sagekv_decode_step_static",
     "sagekv_decode_attn_window", "sagekv_decode_step_window",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read", "sagekv_stage_timing_stages",
     "sagekv_paper_budget",
@@ -96,6 +97,8 @@ def lib():
         L.sagekv_decode_step.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step_ring.restype = ctypes.c_int
         L.sagekv_decode_step_ring.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.sagekv_decode_step_static.restype = ctypes.c_int
+        L.sagekv_decode_step_static.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp]
         L.sagekv_decode_attn_window.restype = ctypes.c_int
         L.sagekv_decode_attn_window.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step_window.restype = ctypes.c_int
@@ -242,6 +245,16 @@ def sagekv_decode_step_ring(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, ring_stat
     _check(lib().sagekv_decode_step_ring(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(Kc), _ptr(Vc),
                                          _ptr(ring_state), _ptr(out), _ptr(workspace), _ws_bytes(workspace),
                                          _stream()), "sagekv_decode_step_ring")
+
+
+STATIC_SCRATCH_BYTES = 4 * 1024 * 1024
+ERR_SCRATCH_LIMIT = 5
+
+
+def sagekv_decode_step_static(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, n_appended: int, out) -> None:
+    """sagekv_decode_step on the library's built-in scratch: no workspace argument, no allocation."""
+    _check(lib().sagekv_decode_step_static(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(Kc), _ptr(Vc),
+                                           n_appended, _ptr(out), _stream()), "sagekv_decode_step_static")
 
 
 def sagekv_decode_attn_window(desc: DecodeDesc, q, q_sink, Kc, Vc, length: int, out, workspace) -> None:

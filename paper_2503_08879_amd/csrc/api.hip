@@ -247,6 +247,30 @@ struct StageTimer {
 
 sagekv_status dev(hipError_t e) { return e == hipSuccess ? SAGEKV_OK : SAGEKV_ERR_DEVICE; }
 
+// Scratch of sagekv_decode_step_static: the split partials of a decode step, for callers that cannot
+// hand over device memory.  Every GPU the library runs on holds its own copy of this array at its
+// own address; in host code the name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[SAGEKV_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, once looked up
+
+// Device address of the scratch array on the current GPU (looked up once per device, with that
+// device current).
+sagekv_status static_scratch(void** ptr) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return SAGEKV_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SAGEKV_ERR_DEVICE;
+    g_scratch_ptr[device] = p;
+  }
+  *ptr = g_scratch_ptr[device];
+  return SAGEKV_OK;
+}
+
 // Every cache and query row is read and written 16 bytes per lane.
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -325,6 +349,7 @@ const char* sagekv_status_string(sagekv_status s) {
     case SAGEKV_ERR_UNSUPPORTED: return "unsupported configuration";
     case SAGEKV_ERR_WORKSPACE: return "workspace missing or too small";
     case SAGEKV_ERR_DEVICE: return "HIP launch failed";
+    case SAGEKV_ERR_SCRATCH_LIMIT: return "problem exceeds the library's built-in scratch (SAGEKV_STATIC_SCRATCH_BYTES)";
   }
   return "unknown status";
 }
@@ -697,6 +722,23 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* d, const void* q, con
   if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
   return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, (int)slot, (int)len, nullptr, out, workspace, workspace_bytes,
                     (hipStream_t)hip_stream);
+}
+
+sagekv_status sagekv_decode_step_static(const sagekv_decode_desc* d, const void* q, const void* k_new, const void* v_new,
+                                        void* Kc, void* Vc, int32_t n_appended, float* out, void* hip_stream) {
+  sagekv_status st;
+  if (!check_decode(d, &st)) return st;
+  if (!q || !k_new || !v_new || !Kc || !Vc || !out || n_appended < 0) return SAGEKV_ERR_INVALID_ARG;
+  const int base = d->n_sink + decode_lists(d) * d->k;
+  const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
+  const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
+  if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
+  if (decode_layout(d).total > (size_t)SAGEKV_STATIC_SCRATCH_BYTES) return SAGEKV_ERR_SCRATCH_LIMIT;
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != SAGEKV_OK) return st;
+  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, (int)slot, (int)len, nullptr, out, ws,
+                    (size_t)SAGEKV_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
 }
 
 sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* d, const void* q, const void* k_new, const void* v_new,
