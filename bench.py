@@ -177,6 +177,25 @@ def layer_sequential(sk, torch, cfg, head_mode, Bt, q_steps, kn_steps, vn_steps,
     ms = timed(graph.replay)
     res["graph_ms_per_token"] = round(ms, 4)
     res["graph_tokens_per_s"] = round(cfg.batch / (ms * 1e-3), 1)
+
+    # the serving-loop form: the append count on the device (one ring state per layer), so the recorded
+    # steps can be replayed for any token
+    rings = torch.zeros((cfg.n_layers, 2), dtype=torch.int32, device="cuda")
+
+    def run_ring():
+        for t in range(n_steps):
+            for l in range(cfg.n_layers):
+                sl = slice(l * lb, (l + 1) * lb)
+                sk.sagekv_decode_step_ring(ldesc, q_steps[t][sl], kn_steps[t][sl], vn_steps[t][sl], Kc[sl], Vc[sl],
+                                           rings[l], out[sl], lws)
+
+    ring_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(ring_graph):
+        run_ring()
+    rings.zero_()
+    ms = timed(ring_graph.replay)
+    res["ring_graph_ms_per_token"] = round(ms, 4)
+    res["ring_graph_tokens_per_s"] = round(cfg.batch / (ms * 1e-3), 1)
     return res
 
 

@@ -143,7 +143,7 @@ sagekv_status sagekv_select_paged(const sagekv_select_desc* desc, const sagekv_p
  *     steps already enqueued there;
  *   - the recent window is then again positions [L - W, L) in ascending order in slots
  *     [S+lists*k, S+lists*k+W): restart the append count (n_appended = 0 for the next
- *     sagekv_decode_step; with sagekv_decode_step_ring set ring_state[0] = ring_state[1] = 0 on the
+ *     sagekv_decode_step; with sagekv_decode_step_ring set ring_state[0] = 0 on the
  *     stream);
  *   - a grown row (grow_recent) starts again at length S+lists*k+W. */
 
@@ -190,9 +190,10 @@ sagekv_status sagekv_decode_step(const sagekv_decode_desc* desc, const void* q, 
  * recorded launch sequence (a HIP graph of a decode step) serves every generated token.
  * ring_state: device int32[2], owned by the caller.  ring_state[0] = tokens appended so far, read by
  * the launch in place of `n_appended` and increased by one when the step is done; ring_state[1] is
- * the library's arrival counter (it is 0 between calls).  Set both to 0 before the first step and
- * after every sagekv_select into this reduced cache (stream-ordered, e.g. a fill kernel: a memset
- * node must not be recorded into a graph).  Calls on one ring_state must not overlap.
+ * the library's arrival counter (it is 0 between calls).  Set both to 0 before the first step;
+ * after every sagekv_select into this reduced cache set ring_state[0] to 0 again (stream-ordered,
+ * e.g. a fill kernel: a memset node must not be recorded into a graph).  Calls on one ring_state
+ * must not overlap.
  * grow_recent: a row that has reached compact_capacity stays as it is (the token is dropped and the
  * count still moves on); the caller sizes compact_capacity for the tokens it will generate. */
 sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* desc, const void* q, const void* k_new,

@@ -278,8 +278,8 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 // derived in the kernels and the launch moves the count on.
 sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void* q_sink, const void* k_new,
                          const void* v_new,
-                         void* Kc, void* Vc, int slot, int len, int32_t* ring, float* out, void* ws, size_t ws_bytes,
-                         hipStream_t s) {
+                         void* Kc, void* Vc, int slot, int len, int32_t* ring, float* out, void* ws,
+                         size_t ws_bytes, hipStream_t s) {
   if (!aligned16(q) || !aligned16(q_sink) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(Kc) ||
       !aligned16(Vc) || ((uintptr_t)out & 3u) || !aligned16(ws) || ((uintptr_t)ring & 3u))
     return SAGEKV_ERR_UNSUPPORTED;
@@ -750,8 +750,8 @@ sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* d, const void* q
   const int base = d->n_sink + decode_lists(d) * d->k;
   // the longest row this step can attend (a growing row's length is only known on the device)
   const int len = d->grow_recent ? d->compact_capacity : base + d->n_recent;
-  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, 0, len, ring_state, out, workspace, workspace_bytes,
-                    (hipStream_t)hip_stream);
+  return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, 0, len, ring_state, out, workspace,
+                    workspace_bytes, (hipStream_t)hip_stream);
 }
 
 sagekv_status sagekv_decode_step_window(const sagekv_decode_desc* d, const void* q, const void* q_sink,

@@ -35,18 +35,66 @@ __device__ __forceinline__ StepGeom step_geom(const DecodeParams& p) {
   return s;
 }
 
-// Rows written by one workgroup each: the last workgroup of the launch to get here advances the
-// device-side count.  Every workgroup has read ring[0] before it takes its ticket (the value went
-// into its addresses), so the store cannot overtake a reader; the next launch on the stream sees
-// it.  Only the counter itself is exchanged between workgroups: relaxed atomics, no cache-wide fence.
-__device__ __forceinline__ void ring_arrive(const DecodeParams& p, const StepGeom& sg) {
-  if (!p.ring || !p.ring_advance || p.n_splits != 1 || threadIdx.x != 0) return;
-  const int total = (int)(gridDim.x * gridDim.y);
+// Called once per row of a launch whose workgroups own whole rows: the last row to finish advances
+// the device-side count (for sliced rows the merge launch does).  Every workgroup has read ring[0] before it gets here (the
+// value went into its addresses), so the store cannot overtake a reader; the next launch on the
+// stream sees it.  Only the counter itself is exchanged between workgroups: relaxed atomics, no
+// cache-wide fence.
+__device__ __forceinline__ void row_done(const DecodeParams& p, const StepGeom& sg) {
+  if (!p.ring || !p.ring_advance) return;
+  const int rows = (int)gridDim.y;
   const int ticket = __hip_atomic_fetch_add(&p.ring[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (ticket == total - 1) {
+  if (ticket == rows - 1) {
     __hip_atomic_store(&p.ring[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(&p.ring[0], sg.n_appended + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+}
+
+// out[head g][dim j] of a row from its slices: sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
+// One pass; the loads of up to 32 slices are all issued before the first is used (one memory round
+// trip), the arithmetic then goes through them eight at a time.
+__device__ __forceinline__ float merge_slices(const DecodeParams& p, int row, int g, int j) {
+  const float* ml = reinterpret_cast<const float*>(p.part_ml + (int64_t)row * p.n_splits * p.G + g);
+  const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g) * p.D + j;
+  float M = -INFINITY, num = 0.f, den = 0.f;
+  for (int s0 = 0; s0 < p.n_splits; s0 += 32) {
+    float vm[32], vl[32], av[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      const int s = s0 + u < p.n_splits ? s0 + u : p.n_splits - 1;
+      vm[u] = ml[(int64_t)s * p.G * 2];
+      vl[u] = ml[(int64_t)s * p.G * 2 + 1];
+      av[u] = a[(int64_t)s * p.G * p.D];
+    }
+#pragma unroll
+    for (int u0 = 0; u0 < 32; u0 += 8) {
+      if (s0 + u0 >= p.n_splits) break;
+      float Mn = M;
+#pragma unroll
+      for (int u = u0; u < u0 + 8; ++u) {
+        if (s0 + u >= p.n_splits) vm[u] = -INFINITY;
+        Mn = fmaxf(Mn, vm[u]);
+      }
+      if (Mn == -INFINITY) continue;  // nothing attended in these slices (uniform over the workgroup)
+      const float f0 = (M == -INFINITY) ? 0.f : exp_fast(M - Mn);
+      num *= f0;
+      den *= f0;
+#pragma unroll
+      for (int u = u0; u < u0 + 8; ++u) {
+        const float f = (vm[u] == -INFINITY) ? 0.f : exp_fast(vm[u] - Mn);
+        num = fmaf(av[u], f, num);
+        den = fmaf(vl[u], f, den);
+      }
+      M = Mn;
+    }
+  }
+  return num / den;
+}
+
+// End of a decode workgroup that owns its whole row: the row is done.  (Sliced rows are completed
+// by the merge launch.)
+__device__ __forceinline__ void finish_row(const DecodeParams& p, const StepGeom& sg) {
+  if (p.n_splits == 1 && threadIdx.x == 0) row_done(p, sg);
 }
 
 template <int DT, int D, int GB, int NW>
@@ -199,7 +247,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
       if (j == 0) pml[g] = make_float2(M, ls);
     }
   }
-  ring_arrive(p, sg);
+  finish_row(p, sg);
 }
 
 // bf16 decode with the q.K products on the matrix cores.  Per 32-token block a wave stages K
@@ -428,7 +476,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
       if (jj == 0) pml[g] = make_float2(M, ls);
     }
   }
-  ring_arrive(p, sg);
+  finish_row(p, sg);
 }
 
 // bf16 decode with BOTH products on the matrix cores.  q.K as in decode_mfma_kernel.  The softmax
@@ -664,47 +712,17 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
       if (jj == 0) pml[g] = make_float2(M, ls);
     }
   }
-  ring_arrive(p, sg);
+  finish_row(p, sg);
 }
 
-// Merges the splits of a row: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
+// Merge launch: the slices of a row -> out (see merge_slices).
 __global__ __launch_bounds__(128) void combine_kernel(DecodeParams p) {
   const int row = blockIdx.x, g = blockIdx.y, j = threadIdx.x;  // one thread per output element
   const int prob = row / p.Hkv, c = row % p.Hkv;
-  const int D = p.D;
   // every slice kernel of the step has finished: the device-side count of appended tokens moves on
   if (p.ring && p.ring_advance && row == 0 && g == 0 && j == 0) p.ring[0] = p.ring[0] + 1;
-  if (j >= D) return;
-  const float2* ml = p.part_ml + (int64_t)row * p.n_splits * p.G + g;
-  const float* a = p.part_acc + ((int64_t)row * p.n_splits * p.G + g) * D + j;
-  // one pass, eight splits at a time: their loads are independent and in flight together
-  float M = -INFINITY, num = 0.f, den = 0.f;
-  for (int s0 = 0; s0 < p.n_splits; s0 += 8) {
-    float2 v[8];
-    float av[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = s0 + u < p.n_splits ? s0 + u : p.n_splits - 1;
-      v[u] = ml[(int64_t)s * p.G];
-      av[u] = a[(int64_t)s * p.G * D];
-      if (s0 + u >= p.n_splits) v[u].x = -INFINITY;
-    }
-    float Mn = M;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) Mn = fmaxf(Mn, v[u].x);
-    if (Mn == -INFINITY) continue;  // nothing attended in these splits (uniform over the workgroup)
-    const float f0 = (M == -INFINITY) ? 0.f : exp_fast(M - Mn);
-    num *= f0;
-    den *= f0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const float f = (v[u].x == -INFINITY) ? 0.f : exp_fast(v[u].x - Mn);
-      num = fmaf(av[u], f, num);
-      den = fmaf(v[u].y, f, den);
-    }
-    M = Mn;
-  }
-  p.out[((int64_t)prob * p.Hq + c * p.G + g) * D + j] = num / den;
+  if (j >= p.D) return;
+  p.out[((int64_t)prob * p.Hq + c * p.G + g) * p.D + j] = merge_slices(p, row, g, j);
 }
 
 template <int LPT>

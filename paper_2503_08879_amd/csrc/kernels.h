@@ -228,8 +228,8 @@ struct DecodeParams {
   int n_splits, tokens_per_split;
   // Device-side ring state (nullable).  ring[0] = tokens appended so far, ring[1] = arrival ticket of
   // the launch that advances it.  When set, slot / len / tokens_per_split above are ignored and
-  // derived from ring[0] in the kernels (see ring_position); with ring_advance the last workgroup
-  // to finish (single-launch rows) or the merge kernel (split rows) stores ring[0] + 1.
+  // derived from ring[0] in the kernels (see ring_position); with ring_advance the workgroup that
+  // completes the last row of the launch (whole rows) or the merge launch (sliced rows) stores ring[0] + 1.
   int* ring;
   int ring_base, ring_W, ring_grow, ring_advance;
   int stream_loads;    // reduced cache larger than the on-chip caches: read it with streaming loads

@@ -28,7 +28,7 @@ def random_reduced_cache(key, P, Hkv, cap, d, dtype):
 @pytest.mark.parametrize(
     "dtype,P,Hq,Hkv,d,S,k,W",
     [
-        (BF16, 2, 8, 2, 128, 4, 700, 24),      # few rows: sliced rows, the merge kernel moves the count on
+        (BF16, 2, 8, 2, 128, 4, 700, 24),      # few rows: sliced rows, the merge launch moves the count on
         (BF16, 100, 8, 2, 128, 4, 150, 9),     # 200 rows, one workgroup each: the last one to finish does
         (BF16, 150, 14, 2, 128, 3, 100, 7),    # 300 rows, G = 7: 4-wave workgroups
         (BF16, 2, 40, 2, 64, 4, 200, 6),       # G = 20: two launches per step, the second moves the count on
