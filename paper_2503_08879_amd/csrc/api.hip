@@ -27,6 +27,7 @@ constexpr float kBand = 1.0f / 4096.0f;
 struct FastPlan {
   bool ok;
   int nA, nB, nC, validA, validC, rank, cap, Gs;
+  int cap_c;  // candidate slots each score chunk owns; what does not fit goes to the row's overflow pool (cap slots)
   int64_t stepB;
   float wA, wB, wC;
 };
@@ -77,14 +78,26 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
     return f;
   }
   f.Gs = (G + 3) / 4 * 4;
+  // A chunk's own slots: twice the candidates an average chunk is expected to keep (rank * wB tokens
+  // per list over the row's chunks), so that only chunks where the candidates crowd (a needle
+  // cluster, the tokens next to the recent window of a trained model) reach into the overflow pool.
+  const int64_t n_chunks = (d->L + kScoreChunk - 1) / kScoreChunk;
+  const double per_chunk = (double)f.rank * (double)f.wB * lists / (double)n_chunks;
+  int cap_c = 32;
+  while (cap_c < 2.0 * per_chunk + 16.0 && cap_c < kScoreChunk) cap_c *= 2;
+  f.cap_c = cap_c;
   return f;
 }
 
 struct SelectLayout {
+  // small: the pre-filtered path applies to the descriptor; rows it cannot certify (and calls that
+  // ask for every score) take the two-sweep dense path, which needs no logit scratch.
+  bool small;
   size_t logits, scores, partials, stats, ghist, total;
-  // fast path
-  size_t samp_logit, samp_stats, samp_tau, cand_count, cand_idx, cand_logit, cand_score, cand_pos, bound,
-      row_fail, fail_list, n_fail;
+  // pre-filtered path
+  size_t samp_logit, samp_stats, samp_tau, cand_count, ovf_count, cand_idx, cand_logit, cand_score, cand_pos,
+      row_fail, n_fail;
+  int64_t slots_per_row, cs_pitch;
   FastPlan fast;
   int64_t Lp;
   int n_chunks, rows, G, n_lists;
@@ -116,16 +129,21 @@ bool check_select(const sagekv_select_desc* d, sagekv_status* st) {
   return true;
 }
 
-// The workspace always holds the dense path's scratch (rows the fast path cannot certify are
-// redone there); a caller-provided scores_out replaces the score rows.
+// Workspace layout.  Descriptors the pre-filtered path cannot serve get the one-sweep dense path's
+// scratch (every token's fp32 logits: G * 4 bytes per token).  All others get: a score row per
+// selection list (used by the rows that have to be redone, and by calls that ask for scores_out
+// through the caller's array instead), the candidate records (a few slots per score chunk and an
+// overflow pool per row) and small per-row arrays.  The dense candidate arrays of the final
+// selection live in the list's score row while it is not in use.
 SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
-  SelectLayout l;
+  SelectLayout l = {};
   l.rows = d->n_problems * d->n_kv_heads;
   l.G = d->n_q_heads / d->n_kv_heads;
   l.n_lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? l.G : 1;
   l.Lp = (d->L + 3) / 4 * 4;
   l.n_chunks = (int)((d->L + kScoreChunk - 1) / kScoreChunk);
   l.fast = fast_plan(d);
+  l.small = l.fast.ok;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     const size_t at = off;
@@ -133,29 +151,37 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
     return at;
   };
   const size_t rows = (size_t)l.rows;
-  l.logits = take(rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
+  l.logits = take(l.small ? 0 : rows * l.n_chunks * l.G * kScoreChunk * sizeof(float));
   l.partials = take(rows * l.G * l.n_chunks * sizeof(float2));
   l.stats = take(rows * l.G * sizeof(RowStat));
   l.ghist = take(rows * l.n_lists * kHistBins * sizeof(int));
-  if (l.fast.ok) {
+  bool cs_in_scores = false;
+  if (l.small) {
     const FastPlan& f = l.fast;
     const size_t ns = (size_t)64 * (f.nA + f.nB + f.nC);
     l.samp_logit = take(rows * ns * f.Gs * sizeof(float));
     l.samp_stats = take(rows * l.G * sizeof(float2));
     l.samp_tau = take(rows * l.n_lists * sizeof(float));
-    const size_t slots = rows * l.n_chunks * kScoreChunk;  // every token has a slot: chunks cannot overflow
+    l.slots_per_row = (int64_t)l.n_chunks * f.cap_c + f.cap;
     l.cand_count = take(rows * l.n_chunks * sizeof(int));
-    l.cand_idx = take(slots * sizeof(int32_t));
-    l.cand_logit = take(slots * f.Gs * sizeof(float));
-    l.cand_score = take(rows * l.n_lists * f.cap * sizeof(float));
-    l.cand_pos = take(rows * l.n_lists * f.cap * sizeof(int32_t));
-    l.bound = take(rows * l.n_lists * sizeof(float));
+    l.ovf_count = take(rows * sizeof(int));
+    l.cand_idx = take(rows * l.slots_per_row * sizeof(int32_t));
+    l.cand_logit = take(rows * l.slots_per_row * f.Gs * sizeof(float));
     l.row_fail = take(rows * sizeof(int));
-    l.fail_list = take(rows * sizeof(int));
     l.n_fail = take(sizeof(int));
+    cs_in_scores = 2 * (int64_t)f.cap <= l.Lp;
+    l.cs_pitch = cs_in_scores ? l.Lp : f.cap;
+    if (!cs_in_scores) {
+      l.cand_score = take(rows * l.n_lists * f.cap * sizeof(float));
+      l.cand_pos = take(rows * l.n_lists * f.cap * sizeof(int32_t));
+    }
   }
   // last, so that no other offset depends on whether the caller brought its own score rows
   l.scores = take(own_scores ? rows * l.n_lists * l.Lp * sizeof(float) : 0);
+  if (cs_in_scores) {  // the first half of a list's score row: exact scores, the second: token indices
+    l.cand_score = l.scores;
+    l.cand_pos = l.scores + (size_t)l.fast.cap * sizeof(float);
+  }
   l.total = off;
   return l;
 }
@@ -377,8 +403,8 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
   if (!workspace || workspace_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  // per-token scores are only produced by the dense path
-  const bool fast = l.fast.ok && scores_out == nullptr;
+  // per-token scores are only produced by the dense stages
+  const bool fast = l.small && scores_out == nullptr;
 
   RowGeom geo;
   geo.n_problems = d->n_problems;
@@ -390,7 +416,6 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
   geo.L = d->L;
   geo.Lp = l.Lp;
 
-  float* logits = (float*)(ws + l.logits);
   float* scores = scores_out ? scores_out : (float*)(ws + l.scores);
   const int64_t pitch = scores_out ? d->L : l.Lp;
   float2* partials = (float2*)(ws + l.partials);
@@ -400,7 +425,6 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
 
   StageTimer t(0, s);
   hipError_t e;
-  RowGate gate = {nullptr, nullptr};
 
   ScoreParams sp = {};
   sp.geo = geo;
@@ -410,30 +434,52 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
   sp.ks_head = d->k_stride_head;
   sp.ks_token = d->k_stride_token;
   sp.pm = pm;
-  sp.logits = logits;
+  sp.logits = (float*)(ws + l.logits);
   sp.partials = partials;
   sp.n_chunks = l.n_chunks;
   sp.g0 = 0;
   sp.scale = scale;
+  sp.stats = stats;
+  sp.scores = scores;
+  sp.pitch = pitch;
+  sp.ghist = ghist;
+  sp.S = d->n_sink;
+  sp.W = d->n_recent;
+  sp.n_lists = l.n_lists;
 
   StatsParams tp = {};
   tp.partials = partials;
   tp.stats = stats;
+  tp.ghist = ghist;
   tp.G = l.G;
   tp.n_chunks = l.n_chunks;
   tp.n_lists = l.n_lists;
 
+  TopkParams kp = {};
+  kp.geo = geo;
+  kp.scores = scores;
+  kp.pitch = pitch;
+  kp.ghist = ghist;
+  kp.stats = stats;
+  kp.q_last = q_last;
+  kp.K = K;
+  kp.ks_problem = d->k_stride_problem;
+  kp.ks_head = d->k_stride_head;
+  kp.ks_token = d->k_stride_token;
+  kp.pm = pm;
+  kp.kept_idx = kept_idx;
+  kp.S = d->n_sink;
+  kp.W = d->n_recent;
+  kp.k = d->k;
+  kp.n_lists = l.n_lists;
+  kp.band = kBand;
+
   if (fast) {
+    // ---- pre-filtered path: sample, one filtering pass over K, selection among the candidates
     const FastPlan& f = l.fast;
     float2* samp_stats = (float2*)(ws + l.samp_stats);
     float* samp_tau = (float*)(ws + l.samp_tau);
-    int* cand_count = (int*)(ws + l.cand_count);
-    int32_t* cand_idx = (int32_t*)(ws + l.cand_idx);
-    float* cand_logit = (float*)(ws + l.cand_logit);
-    float* bound = (float*)(ws + l.bound);
     int* row_fail = (int*)(ws + l.row_fail);
-    int* fail_list = (int*)(ws + l.fail_list);
-    int* n_fail = (int*)(ws + l.n_fail);
 
     SampleParams mp = {};
     mp.geo = geo;
@@ -462,6 +508,8 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     mp.samp_stats = samp_stats;
     mp.samp_tau = samp_tau;
     mp.row_fail = row_fail;
+    mp.ovf_count = (int*)(ws + l.ovf_count);
+    mp.n_fail = (int*)(ws + l.n_fail);
     mp.scale = scale;
     t.begin(SAGEKV_STAGE_SAMPLE);
     e = launch_sample(mp, s);
@@ -471,9 +519,13 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     ScoreParams fp = sp;
     fp.filt.samp_stats = samp_stats;
     fp.filt.samp_tau = samp_tau;
-    fp.filt.cand_count = cand_count;
-    fp.filt.cand_idx = cand_idx;
-    fp.filt.cand_logit = cand_logit;
+    fp.filt.cand_count = (int*)(ws + l.cand_count);
+    fp.filt.ovf_count = (int*)(ws + l.ovf_count);
+    fp.filt.cand_idx = (int32_t*)(ws + l.cand_idx);
+    fp.filt.cand_logit = (float*)(ws + l.cand_logit);
+    fp.filt.cap_c = f.cap_c;
+    fp.filt.cap_o = f.cap;
+    fp.filt.slots_per_row = l.slots_per_row;
     fp.filt.Gs = f.Gs;
     fp.filt.n_lists = l.n_lists;
     fp.filt.S = d->n_sink;
@@ -483,26 +535,23 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     t.end(SAGEKV_STAGE_SCORE);
     if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
 
-    StatsParams ft = tp;
-    ft.ghist = nullptr;
-    ft.samp_stats = samp_stats;
-    ft.samp_tau = samp_tau;
-    ft.bound = bound;
-    t.begin(SAGEKV_STAGE_STATS);
-    e = launch_stats(ft, l.rows, s);
-    t.end(SAGEKV_STAGE_STATS);
-    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
-
     TopkCandParams cp = {};
     cp.geo = geo;
+    cp.partials = partials;
     cp.stats = stats;
-    cp.bound = bound;
-    cp.cand_count = cand_count;
-    cp.cand_idx = cand_idx;
-    cp.cand_logit = cand_logit;
+    cp.samp_stats = samp_stats;
+    cp.samp_tau = samp_tau;
+    cp.ghist = ghist;
+    cp.cand_count = fp.filt.cand_count;
+    cp.cand_idx = fp.filt.cand_idx;
+    cp.cand_logit = fp.filt.cand_logit;
+    cp.cap_c = f.cap_c;
+    cp.cap_o = f.cap;
+    cp.slots_per_row = l.slots_per_row;
     cp.n_chunks = l.n_chunks;
     cp.cand_score = (float*)(ws + l.cand_score);
     cp.cand_pos = (int32_t*)(ws + l.cand_pos);
+    cp.cs_pitch = l.cs_pitch;
     cp.cap = f.cap;
     cp.Gs = f.Gs;
     cp.n_lists = l.n_lists;
@@ -514,78 +563,77 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     cp.pm = pm;
     cp.kept_idx = kept_idx;
     cp.row_fail = row_fail;
+    cp.n_fail = (int*)(ws + l.n_fail);
     cp.S = d->n_sink;
     cp.W = d->n_recent;
     cp.k = d->k;
     cp.band = kBand;
     t.begin(SAGEKV_STAGE_TOPK);
     e = launch_topk_cand(cp, s);
-    if (e == hipSuccess) e = launch_collect_failed(row_fail, l.rows, fail_list, n_fail, s);
     t.end(SAGEKV_STAGE_TOPK);
     if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
-    gate.row_map = fail_list;  // the dense stages below only run for the rows that were flagged
-    gate.n_active = n_fail;
+
+    // Rows that could not be certified: a second pass over their K turns the now exact (M, Z) into
+    // every token's score, then the dense selection.  Both launches are gated by the rows' flags:
+    // with nothing flagged they are a handful of workgroups that look at the flags and leave.
     t.begin(SAGEKV_STAGE_REDO);
+    sp.gate.row_flag = row_fail;
+    sp.gate.n_flagged = (int*)(ws + l.n_fail);
+    e = launch_score(sp, SCORE_SCORES, s);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    kp.gate = sp.gate;
+    e = launch_topk(kp, s);
+    t.end(SAGEKV_STAGE_REDO);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+  } else if (l.small) {
+    // ---- every score is asked for, no logit scratch: two sweeps over K (partials, then scores)
+    if (launch_fill_u32(ws + l.n_fail, 1, 0xFFFFFFFFu, s) != hipSuccess) return SAGEKV_ERR_DEVICE;
+    t.begin(SAGEKV_STAGE_SCORE);
+    e = launch_score(sp, SCORE_PARTIALS, s);
+    t.end(SAGEKV_STAGE_SCORE);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    t.begin(SAGEKV_STAGE_STATS);
+    e = launch_stats(tp, l.rows, s);
+    t.end(SAGEKV_STAGE_STATS);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    t.begin(SAGEKV_STAGE_COMBINE);
+    e = launch_score(sp, SCORE_SCORES, s);
+    t.end(SAGEKV_STAGE_COMBINE);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    t.begin(SAGEKV_STAGE_TOPK);
+    e = launch_topk(kp, s);
+    t.end(SAGEKV_STAGE_TOPK);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+  } else {
+    // ---- one-sweep dense path: logits to scratch, statistics, scores, selection
+    t.begin(SAGEKV_STAGE_SCORE);
+    e = launch_score(sp, SCORE_LOGITS, s);
+    t.end(SAGEKV_STAGE_SCORE);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    t.begin(SAGEKV_STAGE_STATS);
+    e = launch_stats(tp, l.rows, s);
+    t.end(SAGEKV_STAGE_STATS);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    CombineParams cp = {};
+    cp.geo = geo;
+    cp.logits = sp.logits;
+    cp.n_chunks = l.n_chunks;
+    cp.stats = stats;
+    cp.scores = scores;
+    cp.pitch = pitch;
+    cp.ghist = ghist;
+    cp.S = d->n_sink;
+    cp.W = d->n_recent;
+    cp.n_lists = l.n_lists;
+    t.begin(SAGEKV_STAGE_COMBINE);
+    e = launch_combine(cp, s);
+    t.end(SAGEKV_STAGE_COMBINE);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    t.begin(SAGEKV_STAGE_TOPK);
+    e = launch_topk(kp, s);
+    t.end(SAGEKV_STAGE_TOPK);
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
   }
-
-  // a dense call on a descriptor the fast path could serve: sagekv_select_redone_rows must say "dense"
-  if (!fast && l.fast.ok && launch_fill_u32(ws + l.n_fail, 1, 0xFFFFFFFFu, s) != hipSuccess) return SAGEKV_ERR_DEVICE;
-
-  // ---- dense path: every row, or the rows the fast path flagged
-  sp.gate = gate;
-  if (!fast) t.begin(SAGEKV_STAGE_SCORE);
-  e = launch_score(sp, s);
-  if (!fast) t.end(SAGEKV_STAGE_SCORE);
-  if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
-
-  tp.gate = gate;
-  tp.ghist = ghist;
-  if (!fast) t.begin(SAGEKV_STAGE_STATS);
-  e = launch_stats(tp, l.rows, s);
-  if (!fast) t.end(SAGEKV_STAGE_STATS);
-  if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
-
-  CombineParams cp = {};
-  cp.geo = geo;
-  cp.gate = gate;
-  cp.logits = logits;
-  cp.n_chunks = l.n_chunks;
-  cp.stats = stats;
-  cp.scores = scores;
-  cp.pitch = pitch;
-  cp.ghist = ghist;
-  cp.S = d->n_sink;
-  cp.W = d->n_recent;
-  cp.n_lists = l.n_lists;
-  if (!fast) t.begin(SAGEKV_STAGE_COMBINE);
-  e = launch_combine(cp, s);
-  if (!fast) t.end(SAGEKV_STAGE_COMBINE);
-  if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
-
-  TopkParams kp = {};
-  kp.geo = geo;
-  kp.gate = gate;
-  kp.scores = scores;
-  kp.pitch = pitch;
-  kp.ghist = ghist;
-  kp.stats = stats;
-  kp.q_last = q_last;
-  kp.K = K;
-  kp.ks_problem = d->k_stride_problem;
-  kp.ks_head = d->k_stride_head;
-  kp.ks_token = d->k_stride_token;
-  kp.pm = pm;
-  kp.kept_idx = kept_idx;
-  kp.S = d->n_sink;
-  kp.W = d->n_recent;
-  kp.k = d->k;
-  kp.n_lists = l.n_lists;
-  kp.band = kBand;
-  if (!fast) t.begin(SAGEKV_STAGE_TOPK);
-  e = launch_topk(kp, s);
-  if (!fast) t.end(SAGEKV_STAGE_TOPK);
-  if (fast) t.end(SAGEKV_STAGE_REDO);
-  if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
 
   GatherParams gp = {};
   gp.geo = geo;
@@ -652,13 +700,13 @@ sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* d, const void*
   const SelectLayout l = select_layout(d, true);
   if (!workspace || workspace_bytes < l.total) return SAGEKV_ERR_WORKSPACE;
   *n_rows = -1;
-  if (!l.fast.ok) return SAGEKV_OK;
+  if (!l.small) return SAGEKV_OK;
   hipStream_t s = (hipStream_t)hip_stream;
   if (hipStreamSynchronize(s) != hipSuccess) return SAGEKV_ERR_DEVICE;
-  int v = 0;
-  if (hipMemcpy(&v, (const char*)workspace + l.n_fail, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
+  int n = 0;  // -1: the last call went through the dense stages for every row
+  if (hipMemcpy(&n, (const char*)workspace + l.n_fail, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
     return SAGEKV_ERR_DEVICE;
-  *n_rows = v;
+  *n_rows = n;
   return SAGEKV_OK;
 }
 

@@ -62,11 +62,13 @@ inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, uint64_t* don
   return e;
 }
 
-// Rows a gated launch works on: row = row_map[blockIdx] while blockIdx < *n_active (both device
-// memory).  Null row_map = all rows, identity.
+// Rows a gated launch works on: those whose flag is nonzero (device memory, one int per row; set by
+// the pre-filtered path for the rows it could not certify).  Null = every row.  A gated launch has a
+// few row blocks that walk over all rows and skip the unflagged ones, so a launch with nothing to
+// do costs a handful of workgroups.
 struct RowGate {
-  const int* row_map;
-  const int* n_active;
+  const int* row_flag;
+  const int* n_flagged;  // how many flags are set (one int): a gated launch looks here first
 };
 
 // Candidate pre-filter of the fast eviction path.  A strided sample of the row gives approximate
@@ -78,39 +80,57 @@ struct FilterParams {
   const float* samp_tau;     // [rows * n_lists] threshold on the approximate score (per head if n_lists = G)
   int n_lists;               // 1: the group's summed score is compared; G: a token passes if ANY head's
                              //    own probability reaches that head's threshold
-  int* cand_count;           // [rows][n_chunks]               candidates each score workgroup kept
-  int32_t* cand_idx;         // [rows][n_chunks][kScoreChunk]  a workgroup owns its chunk's slots: no
-  float* cand_logit;         // [rows][n_chunks][kScoreChunk][Gs]   global atomics, no overflow
+  // Candidate records (token index + exact fp32 logits of the Gs heads).  Each score workgroup owns
+  // cap_c slots for its chunk (an LDS counter hands them out: no global atomics); a chunk that keeps
+  // more spills into the row's overflow pool of cap_o slots through one global counter per row.
+  // Row r: slots [r * slots_per_row, +n_chunks * cap_c) by chunk, then cap_o overflow slots.
+  int* cand_count;           // [rows][n_chunks]  tokens each chunk kept (may exceed cap_c: the rest overflowed)
+  int* ovf_count;            // [rows]            tokens sent to the overflow pool (may exceed cap_o: dropped,
+                             //                   the row then has more candidates than planned and is redone)
+  int32_t* cand_idx;         // [rows][slots_per_row]
+  float* cand_logit;         // [rows][slots_per_row][Gs]
+  int cap_c, cap_o;
+  int64_t slots_per_row;
   int Gs;
   int S, W;
+};
+
+// What a pass over K leaves behind.
+enum ScoreMode : int {
+  SCORE_LOGITS = 0,    // every token's fp32 logits + softmax partials per chunk (one-sweep dense path)
+  SCORE_FILTER = 1,    // softmax partials + candidate records of the tokens that pass the sample threshold
+  SCORE_PARTIALS = 2,  // softmax partials only (first sweep of the two-sweep dense path)
+  SCORE_SCORES = 3,    // every token's score from known (M, Z) + first radix histogram (second sweep)
 };
 
 struct ScoreParams {
   RowGeom geo;
   RowGate gate;
-  FilterParams filt;  // used by the filtering variant only
+  FilterParams filt;  // SCORE_FILTER only
   const void* q_last;
   const void* K;
   int64_t ks_problem, ks_head, ks_token;  // elements
   PageMap pm;
-  float* logits;                          // [rows][n_chunks][G][kScoreChunk]
+  float* logits;                          // SCORE_LOGITS: [rows][n_chunks][G][kScoreChunk]
   float2* partials;                       // [rows][G][n_chunks]  (max, sum exp(x - max))
   int n_chunks;
   int g0;  // first head of the group handled by this launch
   float scale;
+  // SCORE_SCORES: score[i] = sum_g exp(l[g][i] - M_g) / Z_g (or one row per head), histogram of the
+  // candidates' first radix digit added to ghist (zeroed beforehand)
+  const RowStat* stats;  // [rows][G]
+  float* scores;         // [rows * n_lists][pitch]
+  int64_t pitch;
+  int* ghist;            // [rows * n_lists][kHistBins]
+  int S, W, n_lists;
 };
 
 struct StatsParams {
-  RowGate gate;
   const float2* partials;
   RowStat* stats;  // [rows][G]
   int* ghist;      // [rows * n_lists][kHistBins], zeroed here (nullable)
   int G, n_chunks;
   int n_lists;     // selection lists per row: 1 (group-sum) or G (per-query)
-  // fast path (nullable): bound[list] = upper bound of the exact score of any token the filter dropped
-  const float2* samp_stats;
-  const float* samp_tau;
-  float* bound;  // [rows * n_lists]
 };
 
 struct CombineParams {
@@ -166,6 +186,8 @@ struct SampleParams {
   float2* samp_stats;   // out [rows][G]
   float* samp_tau;      // out [rows * n_lists]
   int* row_fail;        // out [rows] = 0
+  int* ovf_count;       // out [rows] = 0
+  int* n_fail;          // out: 0 rows flagged so far (and: this call runs the pre-filtered path)
   float scale;
 };
 
@@ -182,15 +204,21 @@ __host__ __device__ inline int64_t sample_token(const SampleParams& p, int b, in
 // Final selection of the fast path, on the candidate list of each row.
 struct TopkCandParams {
   RowGeom geo;
-  const RowStat* stats;
-  const float* bound;
-  const int* cand_count;     // per score chunk, see FilterParams
+  const float2* partials;    // [rows][G][n_chunks] exact softmax partials of the filtering pass
+  RowStat* stats;            // out [rows][G]: exact (M, Z), merged here in fp64
+  const float2* samp_stats;  // sample statistics and thresholds, for the bound on a dropped token's score
+  const float* samp_tau;
+  int* ghist;                // [rows * n_lists][kHistBins]: zeroed here for the dense stages that may follow
+  const int* cand_count;     // see FilterParams
   const int32_t* cand_idx;
   const float* cand_logit;
+  int cap_c, cap_o;
+  int64_t slots_per_row;
   int n_chunks;
-  float* cand_score;         // [rows * n_lists][cap] scratch: exact scores of the candidates, dense
-  int32_t* cand_pos;         // [rows * n_lists][cap] scratch: their token indices
-  int cap, Gs;
+  float* cand_score;         // [rows * n_lists][cs_pitch] scratch: exact scores of the candidates, dense
+  int32_t* cand_pos;         // [rows * n_lists][cs_pitch] scratch: their token indices
+  int64_t cs_pitch;          // floats between the lists' scratch rows (>= cap)
+  int cap, Gs;               // cap: candidates a row may have; more = redo
   int n_lists;               // 1 or G: list g of a row ranks head g's own probability
   const void* q_last;
   const void* K;
@@ -198,6 +226,7 @@ struct TopkCandParams {
   PageMap pm;
   int32_t* kept_idx;
   int* row_fail;  // nonzero (a reason code) when the row must be redone by the general path
+  int* n_fail;    // number of flagged rows, incremented with the flag
   int S, W, k;
   float band;
 };
@@ -246,8 +275,7 @@ hipError_t launch_sample(const SampleParams& p, hipStream_t s);         // logit
 hipError_t launch_sample_logits(const SampleParams& p, hipStream_t s);
 hipError_t launch_score_filter(const ScoreParams& p, hipStream_t s);
 hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s);
-hipError_t launch_collect_failed(const int* row_fail, int rows, int* fail_list, int* n_fail, hipStream_t s);
-hipError_t launch_score(const ScoreParams& p, hipStream_t s);
+hipError_t launch_score(const ScoreParams& p, ScoreMode mode, hipStream_t s);  // any mode but SCORE_FILTER
 hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 hipError_t launch_topk(const TopkParams& p, hipStream_t s);

@@ -17,6 +17,28 @@ struct TopkShared {
   int pick_rem;
 };
 
+// Exact softmax statistics of one head of a row from its per-chunk partials (max, sum exp(x - max)):
+// M = overall maximum of the fp32 logits, Z = sum_i exp(l_i - M) combined in fp64.  Called by all 64
+// lanes of a wave; every lane gets the result.
+__device__ inline RowStat merge_partials_wave(const float2* pr, int n_chunks) {
+  const int lane = threadIdx.x & 63;
+  float M = -INFINITY;
+  for (int i = lane; i < n_chunks; i += 64) M = fmaxf(M, pr[i].x);
+  M = wave_max(M);
+  double z = 0.0;
+  for (int i = lane; i < n_chunks; i += 64) {
+    const float2 v = pr[i];
+    z += (double)v.y * exp((double)v.x - (double)M);
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) z += __shfl_xor(z, o);
+  RowStat st;
+  st.M = M;
+  st.Z = z;
+  st.invZ = (float)(1.0 / z);
+  return st;
+}
+
 // Largest digit b such that count(digits >= b) >= k_rem; returns b and the rank left inside it.
 __device__ inline void pick_digit(TopkShared& sh, int nb, int k_rem, int* bin, int* rem) {
   const int t = threadIdx.x;
@@ -127,10 +149,11 @@ __device__ inline double elem_f64<DT_F32>(const void* base, int64_t i) {
 }
 
 // Score of token `tok` of the row in fp64 (heads g_lo .. g_hi-1 of the group), rounded once to fp32.
+// row_stats: the exact (M, Z) of the row's G heads (global or LDS).
 template <int DT>
 __device__ inline float refined_score(const RowGeom& geo, const void* q_last, const void* K, const PageMap& pm,
-                                   int64_t ks_problem, int64_t ks_head, int64_t ks_token, const RowStat* stats,
-                                   int prob, int c, int row, int64_t tok, int g_lo, int g_hi) {
+                                   int64_t ks_problem, int64_t ks_head, int64_t ks_token, const RowStat* row_stats,
+                                   int prob, int c, int64_t tok, int g_lo, int g_hi) {
   const int D = geo.D, G = geo.G;
   const int64_t k_off = kv_offset(pm, pm.ks_page, ks_problem, ks_head, ks_token, prob, c, tok);
   const double inv = 1.0 / sqrt((double)D);
@@ -139,7 +162,7 @@ __device__ inline float refined_score(const RowGeom& geo, const void* q_last, co
     const int64_t q_off = ((int64_t)prob * geo.Hq + c * G + g) * D;
     double acc = 0.0;
     for (int j = 0; j < D; ++j) acc += elem_f64<DT>(q_last, q_off + j) * elem_f64<DT>(K, k_off + j);
-    const RowStat st = stats[(int64_t)row * G + g];
+    const RowStat st = row_stats[g];
     tot += exp(acc * inv - (double)st.M) / st.Z;
   }
   return (float)tot;
@@ -149,8 +172,8 @@ __device__ inline float refined_score(const RowGeom& geo, const void* q_last, co
 // sum order differs from the sequential one by ~1e-16 relative, far below fp32 rounding).
 template <int DT>
 __device__ inline float refined_score_wave(const RowGeom& geo, const void* q_last, const void* K, const PageMap& pm,
-                                        int64_t ks_problem, int64_t ks_head, int64_t ks_token, const RowStat* stats,
-                                        int prob, int c, int row, int64_t tok, int g_lo, int g_hi) {
+                                        int64_t ks_problem, int64_t ks_head, int64_t ks_token, const RowStat* row_stats,
+                                        int prob, int c, int64_t tok, int g_lo, int g_hi) {
   const int D = geo.D, G = geo.G, lane = threadIdx.x & 63;
   const int64_t k_off = kv_offset(pm, pm.ks_page, ks_problem, ks_head, ks_token, prob, c, tok);
   const double inv = 1.0 / sqrt((double)D);
@@ -161,7 +184,7 @@ __device__ inline float refined_score_wave(const RowGeom& geo, const void* q_las
     for (int j = lane; j < D; j += 64) acc += elem_f64<DT>(q_last, q_off + j) * elem_f64<DT>(K, k_off + j);
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
-    const RowStat st = stats[(int64_t)row * G + g];
+    const RowStat st = row_stats[g];
     tot += exp(acc * inv - (double)st.M) / st.Z;
   }
   return (float)tot;

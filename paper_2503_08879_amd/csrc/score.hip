@@ -1,16 +1,20 @@
 // Eviction pass, scoring stage (paper Sec. 2 Step 2: attention scores of the last token's
 // query against the cached keys).
 //
-//   score_kernel, score_mfma_kernel
-//                   stream K once: logit[g][i] = q[g].K[i]/sqrt(d) for the G heads of a row, per-chunk
-//                   softmax partials (max, sum exp); fp32 logits to scratch (dense path) or only the
-//                   tokens that pass the sample threshold, to the chunk's candidate slots (FILTER).
+//   score_kernel (fp32), score_mfma_kernel (bf16)
+//                   stream K once: logit[g][i] = q[g].K[i]/sqrt(d) for the G heads of a row.  What a
+//                   pass leaves behind depends on its mode (ScoreMode): fp32 logits + per-chunk softmax
+//                   partials (max, sum exp) for the one-sweep dense path; partials + the records of
+//                   the tokens that pass the sample threshold (pre-filtered path); partials only, or
+//                   every token's score from known (M, Z) (two-sweep dense path: rows the pre-filter
+//                   could not certify, without a logit scratch).
 //   sample_logits_kernel  logits of the sampled blocks of the pre-filtered path.
 //   stats_kernel    merges the partials of a row into (M, Z) per head, in fp64.
 //   combine_kernel  score[i] = sum_g exp(logit[g][i] - M_g) / Z_g  (fp32) and the first radix
 //                   histogram of the candidates' scores, merged across workgroups with atomics.
 #include "device_utils.h"
 #include "kernels.h"
+#include "radix_select.h"
 
 namespace sagekv {
 
@@ -40,11 +44,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
   constexpr int TPL = 64 / LPT;
   constexpr int SB = LPT < 8 ? LPT : 8;  // loads in flight per batch
 
-  int row = blockIdx.y;
-  if (p.gate.row_map) {
-    if ((int)blockIdx.y >= *p.gate.n_active) return;
-    row = p.gate.row_map[blockIdx.y];
-  }
+  const int row = blockIdx.y;
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tq = lane / LPT, cl = lane % LPT;
@@ -137,14 +137,20 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
 // 16: 16/GPAD tiles share an accumulator (the queries of tile t sit in rows t*GPAD..), so after
 // a block every lane owns 4 logits and all stores are coalesced.
 //
-// FILTER = true is the fast eviction path: nothing is written per token.  A lane keeps its logits
-// only for tokens whose approximate score (sample statistics) reaches the row's conservative
-// threshold, and appends (index, logits) to the row's candidate list.
+// MODE (ScoreMode) says what the pass leaves behind:
+//   SCORE_LOGITS    every logit, to the scratch of the one-sweep dense path, and the softmax partials;
+//   SCORE_FILTER    the pre-filtered path: nothing is written per token.  A lane keeps its logits only for
+//                   tokens whose approximate score (sample statistics) reaches the row's conservative
+//                   threshold, and appends (index, logits) to the chunk's candidate slots, or, once those
+//                   are used up, to the row's overflow pool;
+//   SCORE_PARTIALS  the softmax partials only;
+//   SCORE_SCORES    with (M, Z) of every head known: every token's score (summed over the group, or one
+//                   row per head), and the first radix histogram of the candidates' scores.
 //
 // PAGED: the chunk's pages (at most 64: pages hold 16 tokens or more) are looked up once, one per
 // lane, and every load takes its page from the lane that holds it.
 // One score chunk (kScoreChunk tokens of row `row`) by one workgroup of kScoreThreads threads.
-template <int D, int GPAD, bool FILTER, bool PAGED>
+template <int D, int GPAD, int MODE, bool PAGED>
 __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, int row, int chunk) {
   constexpr int CH = D / 8;         // 16-byte chunks per token
   constexpr int TPL = 64 / CH;      // tokens per coalesced wave load
@@ -152,6 +158,9 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
   constexpr int KSTEPS = D / 32;    // MFMA k-steps per tile
   constexpr int TILES = 16 / GPAD;  // 16-token tiles per accumulator
   constexpr int NACC = 4 / TILES;   // accumulators per block
+  constexpr bool FILTER = MODE == SCORE_FILTER;
+  constexpr bool KEEP = MODE == SCORE_LOGITS || MODE == SCORE_SCORES;  // per-token values held to the end
+  constexpr bool PARTIALS = MODE != SCORE_SCORES;
 
   __shared__ uint4 lds[kScoreWaves][64 * CH];
   __shared__ float2 part[kScoreWaves][4][4];
@@ -217,7 +226,8 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
     sum[r] = 0.f;
   }
 
-  // filter state: approximate softmax weights of this lane's 4 heads, the row's threshold
+  // softmax weights of this lane's 4 heads: the sample's (M^, 1/Z^) for the filter, the exact (M, 1/Z)
+  // for the scores; the row's filter threshold(s)
   float fM[4] = {0.f, 0.f, 0.f, 0.f}, fInv[4] = {0.f, 0.f, 0.f, 0.f}, ftau = 0.f;
   float ftau_h[4] = {INFINITY, INFINITY, INFINITY, INFINITY};  // per-query lists: a threshold per head
   const bool per_head = FILTER && p.filt.n_lists > 1;
@@ -234,13 +244,25 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
     if (threadIdx.x == 0) n_kept_wg = 0;
     __syncthreads();
   }
-  const int64_t slot_base = ((int64_t)row * p.n_chunks + chunk) * kScoreChunk;  // FILTER: this chunk's slots
+  if (MODE == SCORE_SCORES) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (hbase + r < gb) {
+        const RowStat st = p.stats[(int64_t)row * p.geo.G + p.g0 + hbase + r];
+        fM[r] = st.M;
+        fInv[r] = st.invZ;
+      }
+  }
+  // FILTER: this chunk's own candidate slots, and the row's overflow pool behind all chunks' slots
+  const int64_t row_slots = (int64_t)row * p.filt.slots_per_row;
+  const int64_t slot_base = row_slots + (int64_t)chunk * p.filt.cap_c;
+  const int64_t ovf_base = row_slots + (int64_t)p.n_chunks * p.filt.cap_c;
 
   // Software pipeline: the loads of block b+1 are issued right after block b went to LDS, so
-  // their latency overlaps block b's MFMA phase.  The logits stay in registers until the wave
+  // their latency overlaps block b's MFMA phase.  Per-token results stay in registers until the wave
   // has loaded its last block: loads and stores share one in-order completion counter, so a
   // store inside the loop would put its write-ack latency on the critical path of every block.
-  float xs[FILTER ? 1 : kBlocksPerWave][NACC][4];
+  float xs[KEEP ? kBlocksPerWave : 1][NACC][4];
 #pragma unroll
   for (int blk = 0; blk < kBlocksPerWave; ++blk) {
     const int64_t tok_base = wave_base + (int64_t)blk * kBlockStride;
@@ -285,16 +307,21 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float x = acc[a][r] * p.scale;
-          xs[FILTER ? 0 : blk][a][r] = x;
+          xs[KEEP ? blk : 0][a][r] = x;
           if (tok < L && hbase + r < gb) {
-            const float mn = fmaxf(m[r], x);
-            sum[r] = sum[r] * exp_fast(m[r] - mn) + exp_fast(x - mn);
-            m[r] = mn;
+            if (PARTIALS) {
+              const float mn = fmaxf(m[r], x);
+              sum[r] = sum[r] * exp_fast(m[r] - mn) + exp_fast(x - mn);
+              m[r] = mn;
+            }
             if (FILTER) {
               const float pr = exp_fast(x - fM[r]) * fInv[r];
               approx += pr;
               any_head |= !(pr < ftau_h[r]);
             }
+            if (MODE == SCORE_SCORES) xs[KEEP ? blk : 0][a][r] = exp_times(x - fM[r], fInv[r]);
+          } else if (MODE == SCORE_SCORES) {
+            xs[KEEP ? blk : 0][a][r] = 0.f;
           }
         }
         if (FILTER) {
@@ -316,10 +343,18 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
             if (lane == 0) base = atomicAdd(&n_kept_wg, __popcll(bal));  // LDS counter
             base = __shfl(base, 0);
             int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
-            pos = __shfl(pos, ((j - j % (GPAD / 4)) << 4) | n);  // every lane of the token
-            if (pass && hbase < gb) {
-              if (rep) p.filt.cand_idx[slot_base + pos] = (int32_t)tok;
-              float* rec = p.filt.cand_logit + (slot_base + pos) * p.filt.Gs + hbase;
+            const int src = ((j - j % (GPAD / 4)) << 4) | n;  // the token's counting lane
+            pos = __shfl(pos, src);                           // every lane of the token
+            int64_t slot = slot_base + pos;
+            if (base + __popcll(bal) > p.filt.cap_c) {  // wave-uniform, rare: the chunk's own slots are used up
+              int o = 0;
+              if (pass && rep && pos >= p.filt.cap_c) o = atomicAdd(&p.filt.ovf_count[row], 1);
+              o = __shfl(o, src);
+              if (pos >= p.filt.cap_c) slot = o < p.filt.cap_o ? ovf_base + o : -1;  // pool full: dropped, the row is redone
+            }
+            if (pass && hbase < gb && slot >= 0) {
+              if (rep) p.filt.cand_idx[slot] = (int32_t)tok;
+              float* rec = p.filt.cand_logit + slot * p.filt.Gs + hbase;
               *reinterpret_cast<float4*>(rec) = make_float4(xs[0][a][0], xs[0][a][1], xs[0][a][2], xs[0][a][3]);
             }
           }
@@ -327,16 +362,71 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
       }
     }
   }
+  if (MODE == SCORE_LOGITS) {
 #pragma unroll
-  for (int blk = 0; blk < (FILTER ? 0 : kBlocksPerWave); ++blk) {
+    for (int blk = 0; blk < kBlocksPerWave; ++blk) {
 #pragma unroll
-    for (int a = 0; a < NACC; ++a) {
-      const int64_t tok = wave_base + (int64_t)blk * kBlockStride + (a * TILES + (4 * j) / GPAD) * 16 + n;
+      for (int a = 0; a < NACC; ++a) {
+        const int64_t tok = wave_base + (int64_t)blk * kBlockStride + (a * TILES + (4 * j) / GPAD) * 16 + n;
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (tok < L && hbase + r < gb)
-          p.logits[logit_index(p.geo, p.n_chunks, row, p.g0 + hbase + r, tok)] = xs[blk][a][r];
+        for (int r = 0; r < 4; ++r)
+          if (tok < L && hbase + r < gb)
+            p.logits[logit_index(p.geo, p.n_chunks, row, p.g0 + hbase + r, tok)] = xs[KEEP ? blk : 0][a][r];
+      }
     }
+  }
+  if (MODE == SCORE_SCORES) {
+    // xs holds exp(l - M) / Z of this lane's heads.  One list per row: the group's sum (the lanes that
+    // share a token add up, ascending heads within a lane); one list per head: each value is a score.
+    __shared__ int hist[kHistBins];
+    const bool per_q = p.n_lists > 1;
+    const bool rep = (4 * j) % GPAD == 0;
+    const int64_t cand_lo = p.S, cand_hi = L - p.W;
+    if (!per_q) {
+#pragma unroll
+      for (int blk = 0; blk < kBlocksPerWave; ++blk)
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) {
+          float v = (xs[KEEP ? blk : 0][a][0] + xs[KEEP ? blk : 0][a][1]) + (xs[KEEP ? blk : 0][a][2] + xs[KEEP ? blk : 0][a][3]);
+          if (GPAD >= 8) v += __shfl_xor(v, 16);
+          if (GPAD >= 16) v += __shfl_xor(v, 32);
+          xs[KEEP ? blk : 0][a][0] = v;
+        }
+    }
+    const int n_pass = per_q ? gb : 1;  // histogram passes: one list at a time through the LDS histogram
+    for (int li = 0; li < n_pass; ++li) {
+      for (int b = threadIdx.x; b < kHistBins; b += kScoreThreads) hist[b] = 0;
+      __syncthreads();
+      const int64_t list = (int64_t)row * p.n_lists + (per_q ? p.g0 + li : 0);
+      float* out = p.scores + list * p.pitch;
+      // the lane that holds this list's value of a token: the counting lane (sum), or head li's lane and register
+      const bool mine = per_q ? (hbase <= li && li < hbase + 4) : rep;
+      const int r_sel = per_q ? (li - hbase) & 3 : 0;
+#pragma unroll
+      for (int blk = 0; blk < kBlocksPerWave; ++blk)
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) {
+          const int64_t tok = wave_base + (int64_t)blk * kBlockStride + (a * TILES + (4 * j) / GPAD) * 16 + n;
+          float v = xs[KEEP ? blk : 0][a][0];
+          if (per_q) {
+            v = r_sel == 1 ? xs[KEEP ? blk : 0][a][1] : v;
+            v = r_sel == 2 ? xs[KEEP ? blk : 0][a][2] : v;
+            v = r_sel == 3 ? xs[KEEP ? blk : 0][a][3] : v;
+          }
+          if (mine && tok < L) {
+            out[tok] = v;
+            if (tok >= cand_lo && tok < cand_hi) atomicAdd(&hist[(__float_as_uint(v) >> 20) & (kHistBins - 1)], 1);
+          }
+        }
+      __syncthreads();
+      int* gh = p.ghist + list * kHistBins;
+      for (int b = threadIdx.x; b < kHistBins; b += kScoreThreads) {
+        const int v = hist[b];
+        if (v) atomicAdd(&gh[b], v);
+      }
+      __syncthreads();
+    }
+    return;
   }
 
   // (max, sum) of the chunk: the 16 lanes of a row block share their heads
@@ -345,9 +435,9 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
     float M = m[r];
 #pragma unroll
     for (int o = 8; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-    float s = (m[r] == -INFINITY) ? 0.f : sum[r] * exp_fast(m[r] - M);
-    s = group_sum<16>(s);
-    if (n == 0) part[wave][j][r] = make_float2(M, s);
+    float sm = (m[r] == -INFINITY) ? 0.f : sum[r] * exp_fast(m[r] - M);
+    sm = group_sum<16>(sm);
+    if (n == 0) part[wave][j][r] = make_float2(M, sm);
   }
   __syncthreads();
   if (FILTER && threadIdx.x == 0) p.filt.cand_count[(int64_t)row * p.n_chunks + chunk] = n_kept_wg;
@@ -357,31 +447,33 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
     for (int w = 0; w < kScoreWaves; ++w)
       for (int jj = 0; jj < 4; ++jj)
         if ((4 * jj) % GPAD == (g / 4) * 4) M = fmaxf(M, part[w][jj][g % 4].x);
-    float s = 0.f;
+    float sm = 0.f;
     for (int w = 0; w < kScoreWaves; ++w)
       for (int jj = 0; jj < 4; ++jj)
         if ((4 * jj) % GPAD == (g / 4) * 4) {
           const float2 pw = part[w][jj][g % 4];
-          s += (pw.x == -INFINITY) ? 0.f : pw.y * exp_fast(pw.x - M);
+          sm += (pw.x == -INFINITY) ? 0.f : pw.y * exp_fast(pw.x - M);
         }
-    p.partials[((int64_t)row * p.geo.G + p.g0 + g) * p.n_chunks + chunk] = make_float2(M, s);
+    p.partials[((int64_t)row * p.geo.G + p.g0 + g) * p.n_chunks + chunk] = make_float2(M, sm);
   }
 }
 
 // grid (chunks, rows).  A gated launch (rows the pre-filter could not certify, usually none) has a
-// few y-blocks only, each looping over the active rows: an empty launch then costs a handful of
-// workgroups instead of one per (chunk, row).
-template <int D, int GPAD, bool FILTER, bool PAGED>
+// few y-blocks only, each walking over all rows and working on the flagged ones: an empty launch
+// then costs a handful of workgroups instead of one per (chunk, row).
+template <int D, int GPAD, int MODE, bool PAGED>
 __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(ScoreParams p, int gb) {
-  if (!FILTER && p.gate.row_map) {
-    const int n_active = *p.gate.n_active;
-    for (int i = blockIdx.y; i < n_active; i += gridDim.y) {
-      score_mfma_chunk<D, GPAD, FILTER, PAGED>(p, gb, p.gate.row_map[i], (int)blockIdx.x);
+  if (MODE != SCORE_FILTER && p.gate.row_flag) {
+    if (*p.gate.n_flagged == 0) return;  // the usual case: nothing to redo
+    const int rows = p.geo.n_problems * p.geo.Hkv;
+    for (int row = blockIdx.y; row < rows; row += gridDim.y) {
+      if (p.gate.row_flag[row] == 0) continue;  // workgroup-uniform
+      score_mfma_chunk<D, GPAD, MODE, PAGED>(p, gb, row, (int)blockIdx.x);
       __syncthreads();  // the chunk's last LDS reads, before the next row's writes
     }
     return;
   }
-  score_mfma_chunk<D, GPAD, FILTER, PAGED>(p, gb, (int)blockIdx.y, (int)blockIdx.x);
+  score_mfma_chunk<D, GPAD, MODE, PAGED>(p, gb, (int)blockIdx.y, (int)blockIdx.x);
 }
 
 // Logits of the sampled blocks (fast path), same MFMA scheme as score_mfma_kernel: one wave per
@@ -450,52 +542,13 @@ __global__ __launch_bounds__(kScoreThreads) void sample_logits_kernel(SamplePara
 }
 
 __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
-  constexpr double kFlushed = 0x1p-126;  // results of the hardware exp2 below this are 0
-  const int lane = threadIdx.x;
-  int row = blockIdx.x;
-  if (p.gate.row_map) {
-    if ((int)blockIdx.x >= *p.gate.n_active) return;
-    row = p.gate.row_map[blockIdx.x];
-  }
+  const int lane = threadIdx.x, row = blockIdx.x;
   if (p.ghist)
     for (int b = lane; b < kHistBins * p.n_lists; b += 64) p.ghist[(int64_t)row * p.n_lists * kHistBins + b] = 0;
-  double rho = 0.0;  // max over heads of (exact softmax weight) / (sampled softmax weight)
-  double flushed = 0.0;  // what the filter's approximate score can miss, see below
   for (int g = 0; g < p.G; ++g) {
-    const float2* pr = p.partials + ((int64_t)row * p.G + g) * p.n_chunks;
-    float M = -INFINITY;
-    for (int i = lane; i < p.n_chunks; i += 64) M = fmaxf(M, pr[i].x);
-    M = wave_max(M);
-    double z = 0.0;
-    for (int i = lane; i < p.n_chunks; i += 64) {
-      float2 v = pr[i];
-      z += (double)v.y * exp((double)v.x - (double)M);
-    }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) z += __shfl_xor(z, o);
-    if (lane == 0) {
-      RowStat st;
-      st.M = M;
-      st.Z = z;
-      st.invZ = (float)(1.0 / z);
-      p.stats[(int64_t)row * p.G + g] = st;
-      if (p.bound) {
-        const float2 ss = p.samp_stats[(int64_t)row * p.G + g];
-        const double r = exp((double)ss.x - (double)M) / (z * (double)ss.y);
-        rho = r > rho || !(r == r) ? r : rho;
-        flushed += kFlushed * (double)ss.y;
-        if (p.n_lists > 1)  // per-query lists: head g's own bound
-          p.bound[(int64_t)row * p.n_lists + g] =
-              (float)(r * ((double)p.samp_tau[(int64_t)row * p.n_lists + g] + kFlushed * (double)ss.y) * 1.001);
-      }
-    }
+    const RowStat st = merge_partials_wave(p.partials + ((int64_t)row * p.G + g) * p.n_chunks, p.n_chunks);
+    if (lane == 0) p.stats[(int64_t)row * p.G + g] = st;
   }
-  // A token the filter dropped had approximate score < tau^; its exact score is below rho * tau^
-  // (plus fp32 slack).  The candidate selection checks its threshold against this bound.  The
-  // filter's exponentials come out as 0 below 2^-126 (hardware exp2), so a dropped token's true
-  // approximate score may exceed the computed one by up to 2^-126 / Z^ per head.
-  if (p.bound && p.n_lists == 1 && lane == 0)
-    p.bound[row] = (float)(rho * ((double)p.samp_tau[row] + flushed) * 1.001);
 }
 
 constexpr int kCombineThreads = 256;
@@ -505,12 +558,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
   __shared__ int hist[kHistBins];
   __shared__ float sM[kMaxG], sInv[kMaxG];
   const int tid = threadIdx.x;
-  // a gated launch has a few y-blocks, each looping over the active rows (see score_mfma_kernel)
-  const bool gated = p.gate.row_map != nullptr;
-  const int n_active = gated ? *p.gate.n_active : 0;
-  for (int ry = blockIdx.y; !gated || ry < n_active; ry += gridDim.y) {
-  const int row = gated ? p.gate.row_map[ry] : ry;
-
+  const int row = blockIdx.y;
   const int G = p.geo.G;
   const int64_t L = p.geo.L;
   for (int b = tid; b < kHistBins; b += kCombineThreads) hist[b] = 0;
@@ -559,9 +607,6 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(CombineParams 
     int v = hist[b];
     if (v) atomicAdd(&gh[b], v);
   }
-  if (!gated) break;
-  __syncthreads();  // hist and the statistics are rewritten for the next row
-  }
 }
 
 template <int DT, int D>
@@ -580,21 +625,26 @@ hipError_t launch_score_g(const ScoreParams& p, int gb, dim3 grid, hipStream_t s
   return hipGetLastError();
 }
 
-template <int D, bool FILTER, bool PAGED>
+template <int D, int MODE, bool PAGED>
 hipError_t launch_score_mfma_p(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
   if (gb <= 4)
-    hipLaunchKernelGGL((score_mfma_kernel<D, 4, FILTER, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
+    hipLaunchKernelGGL((score_mfma_kernel<D, 4, MODE, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
   else if (gb <= 8)
-    hipLaunchKernelGGL((score_mfma_kernel<D, 8, FILTER, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
+    hipLaunchKernelGGL((score_mfma_kernel<D, 8, MODE, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
   else
-    hipLaunchKernelGGL((score_mfma_kernel<D, 16, FILTER, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
+    hipLaunchKernelGGL((score_mfma_kernel<D, 16, MODE, PAGED>), grid, dim3(kScoreThreads), 0, s, p, gb);
   return hipGetLastError();
 }
 
-template <int D, bool FILTER>
+template <int D, int MODE>
 hipError_t launch_score_mfma(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
-  return p.pm.table ? launch_score_mfma_p<D, FILTER, true>(p, gb, grid, s)
-                    : launch_score_mfma_p<D, FILTER, false>(p, gb, grid, s);
+  return p.pm.table ? launch_score_mfma_p<D, MODE, true>(p, gb, grid, s)
+                    : launch_score_mfma_p<D, MODE, false>(p, gb, grid, s);
+}
+
+template <int MODE>
+hipError_t launch_score_mfma_d(const ScoreParams& p, int gb, dim3 grid, hipStream_t s) {
+  return p.geo.D == 128 ? launch_score_mfma<128, MODE>(p, gb, grid, s) : launch_score_mfma<64, MODE>(p, gb, grid, s);
 }
 
 }  // namespace
@@ -605,9 +655,9 @@ hipError_t launch_score_filter(const ScoreParams& p0, hipStream_t s) {
   dim3 grid((unsigned)p0.n_chunks, (unsigned)rows);
   ScoreParams p = p0;
   p.g0 = 0;
+  p.gate.row_flag = nullptr;
   if (p.geo.dtype != DT_BF16 || p.geo.G > 16) return hipErrorInvalidValue;
-  return p.geo.D == 128 ? launch_score_mfma<128, true>(p, p.geo.G, grid, s)
-                        : launch_score_mfma<64, true>(p, p.geo.G, grid, s);
+  return launch_score_mfma_d<SCORE_FILTER>(p, p.geo.G, grid, s);
 }
 
 hipError_t launch_sample_logits(const SampleParams& p, hipStream_t s) {
@@ -627,21 +677,26 @@ hipError_t launch_sample_logits(const SampleParams& p, hipStream_t s) {
 
 int max_group_per_launch() { return 8; }
 
-hipError_t launch_score(const ScoreParams& p0, hipStream_t s) {
+// Dense passes.  bf16: any mode, gated or not; fp32 caches: SCORE_LOGITS over every row only.
+hipError_t launch_score(const ScoreParams& p0, ScoreMode mode, hipStream_t s) {
   const int rows = p0.geo.n_problems * p0.geo.Hkv;
-  // gated bf16 launches loop over the active rows in the kernel (the fp32 kernel has one y-block per row)
-  const bool few = p0.gate.row_map && p0.geo.dtype == DT_BF16;
-  dim3 grid((unsigned)p0.n_chunks, (unsigned)(few && rows > kGatedRowBlocks ? kGatedRowBlocks : rows));
-  const int per_launch = p0.geo.dtype == DT_BF16 ? 16 : max_group_per_launch();
+  const bool bf16 = p0.geo.dtype == DT_BF16;
+  if (mode == SCORE_FILTER || (!bf16 && (mode != SCORE_LOGITS || p0.gate.row_flag))) return hipErrorInvalidValue;
+  dim3 grid((unsigned)p0.n_chunks, (unsigned)(p0.gate.row_flag && rows > kGatedRowBlocks ? kGatedRowBlocks : rows));
+  const int per_launch = bf16 ? 16 : max_group_per_launch();
   for (int g0 = 0; g0 < p0.geo.G; g0 += per_launch) {
     ScoreParams p = p0;
     p.g0 = g0;
     const int gb = p0.geo.G - g0 < per_launch ? p0.geo.G - g0 : per_launch;
     hipError_t e;
-    if (p.geo.dtype == DT_BF16)
-      e = p.geo.D == 128 ? launch_score_mfma<128, false>(p, gb, grid, s) : launch_score_mfma<64, false>(p, gb, grid, s);
-    else
+    if (!bf16)
       e = p.geo.D == 128 ? launch_score_g<DT_F32, 128>(p, gb, grid, s) : launch_score_g<DT_F32, 64>(p, gb, grid, s);
+    else if (mode == SCORE_LOGITS)
+      e = launch_score_mfma_d<SCORE_LOGITS>(p, gb, grid, s);
+    else if (mode == SCORE_PARTIALS)
+      e = launch_score_mfma_d<SCORE_PARTIALS>(p, gb, grid, s);
+    else
+      e = launch_score_mfma_d<SCORE_SCORES>(p, gb, grid, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
@@ -655,8 +710,7 @@ hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s) {
 hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
   const int rows = p.geo.n_problems * p.geo.Hkv;
   const unsigned nx = (unsigned)((p.geo.L + kCombineChunk - 1) / kCombineChunk);
-  const unsigned ny = (unsigned)(p.gate.row_map && rows > kGatedRowBlocks ? kGatedRowBlocks : rows);
-  hipLaunchKernelGGL(combine_kernel, dim3(nx, ny, (unsigned)p.n_lists), dim3(kCombineThreads), 0, s, p);
+  hipLaunchKernelGGL(combine_kernel, dim3(nx, (unsigned)rows, (unsigned)p.n_lists), dim3(kCombineThreads), 0, s, p);
   return hipGetLastError();
 }
 

@@ -110,12 +110,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   __shared__ TopkShared sh;
   extern __shared__ __align__(16) uint32_t bitmap[];  // bit i + head: candidate i is selected (head: see QuadRow)
   const int tid = threadIdx.x;
-  int list = blockIdx.x;  // selection list: one per row (group-sum) or one per (row, query head)
-  if (p.gate.row_map) {
-    if ((int)blockIdx.x / p.n_lists >= *p.gate.n_active) return;
-    list = p.gate.row_map[blockIdx.x / p.n_lists] * p.n_lists + blockIdx.x % p.n_lists;
-  }
+  const int list = blockIdx.x;  // selection list: one per row (group-sum) or one per (row, query head)
   const int row = list / p.n_lists, gl = list % p.n_lists;
+  if (p.gate.row_flag && (*p.gate.n_flagged == 0 || p.gate.row_flag[row] == 0)) return;  // gated launch: only the flagged rows
   const int g_lo = p.n_lists > 1 ? gl : 0, g_hi = p.n_lists > 1 ? gl + 1 : p.geo.G;
   const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
   const int S = p.S, W = p.W, k = p.k;
@@ -125,6 +122,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   int32_t* kept_row = p.kept_idx + (int64_t)row * n_kept;
   int32_t* kept = kept_row + gl * k;  // this list's k slots start at kept[S]
   float* cand = p.scores + (int64_t)list * p.pitch + S;
+  const RowStat* row_stats = p.stats + (int64_t)row * p.geo.G;
 
   if (gl == 0) {
     for (int t = tid; t < S; t += kTopkThreads) kept_row[t] = t;
@@ -219,8 +217,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
     if (nb <= 4 * kTopkWaves) {  // the usual handful: one wave per member
       for (int t = tid >> 6; t < nb; t += kTopkWaves) {
         const int i = band_i[t];
-        const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob,
-                                               c, row, S + i, g_lo, g_hi);
+        const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, row_stats,
+                                               prob, c, S + i, g_lo, g_hi);
         if ((tid & 63) == 0) {
           band_v[t] = v;
           cand[i] = v;
@@ -229,8 +227,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
     } else {
       for (int t = tid; t < nb; t += kTopkThreads) {
         const int i = band_i[t];
-        const float v = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c,
-                                          row, S + i, g_lo, g_hi);
+        const float v = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, row_stats, prob, c,
+                                          S + i, g_lo, g_hi);
         band_v[t] = v;
         cand[i] = v;
       }
@@ -273,8 +271,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
       for (int u = 0; u < 4; ++u) {
         const int i = i0 + u * kTopkThreads;
         if (v[u] >= lo && v[u] <= hi)
-          cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, p.stats, prob, c, row,
-                                      S + i, g_lo, g_hi);
+          cand[i] = refined_score<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, row_stats, prob, c,
+                                          S + i, g_lo, g_hi);
       }
     }
   }

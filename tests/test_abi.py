@@ -33,7 +33,11 @@ def test_status_strings_and_host_side_checks():
     good = sk.SelectDesc(32, 32, 8, 128, 0, 0, 131072, 8 * 131072 * 128, 131072 * 128, 128, 8 * 131072 * 128,
                          131072 * 128, 128, 4, 512, 3580, 4096)
     n = sk.sagekv_select_workspace_bytes(good)
-    assert n > 32 * 8 * 4 * 131072 * 4  # at least the fp32 logits
+    # config C3: a score row per KV head for the rows that have to be redone (128 MiB) + candidate records
+    assert 32 * 8 * 131072 * 4 < n <= 0.35 * 2 ** 30
+    dense = sk.SelectDesc(32, 32, 8, 128, 0, 0, 131072, 8 * 131072 * 128, 131072 * 128, 128, 8 * 131072 * 128,
+                          131072 * 128, 128, 4, 512, 3580, 4096, sk.SELECT_DENSE)
+    assert sk.sagekv_select_workspace_bytes(dense) > 32 * 8 * 4 * 131072 * 4  # the one-sweep dense path keeps fp32 logits
     bad = sk.SelectDesc(32, 32, 8, 128, 0, 0, 131072, 8 * 131072 * 128, 131072 * 128, 128, 8 * 131072 * 128,
                         131072 * 128, 128, 4, 512, 131072, 4096)
     assert sk.sagekv_select_workspace_bytes(bad) == 0

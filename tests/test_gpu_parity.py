@@ -380,6 +380,52 @@ def test_select_ranks_scores_below_the_normal_range_prefiltered(ref, head_mode, 
     assert out["redone"] >= 0  # the call went through the pre-filtered path
 
 
+def test_prefilter_chunk_slots_overflow_into_the_row_pool(ref):
+    """Every score chunk owns a few candidate slots; here the heavy tokens all sit in two chunks (as the
+    tokens next to the recent window do in a trained model), far more than those chunks' own slots hold,
+    so most candidates go through the row's overflow pool.  The kept set is still the oracle's and the
+    rows are certified without the dense stages."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 40000, 4, 128, 1000
+    G = Hq // Hkv
+    q, K, V = rand_case(91, P, Hq, Hkv, d, L, BF16)
+    q64 = synth.to_f64(q, BF16)
+    K64 = synth.to_f64(K, BF16)
+    qdir = q64.reshape(P, Hkv, G, d).mean(2)
+    qdir /= np.linalg.norm(qdir, axis=-1, keepdims=True)
+    # tokens 37000 .. 38799 (chunks 36 and 37 of 1024 tokens): +3 logits or so on every head of the group
+    K64[:, :, 37000:38800] += 3.0 * np.sqrt(G) * qdir[:, :, None, :]
+    K = synth.round_to_dtype(K64, BF16)
+    Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    inside = ((kept[0, :, S:S + k] >= 37000) & (kept[0, :, S:S + k] < 38800)).sum(axis=-1)
+    assert (inside > 700).all(), inside  # the selection is mostly that cluster: 350 tokens a chunk against 64-128 slots
+    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=False)
+    assert out["redone"] == 0
+    n_ex = gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k)
+    if n_ex == 0:
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
+
+
+def test_scores_out_without_the_dense_flag_takes_two_sweeps(ref):
+    """A call that asks for every score on a descriptor the pre-filtered path serves has no logit scratch:
+    it reads K twice (softmax statistics, then scores).  Scores and kept sets as the oracle's, and as
+    the one-sweep dense path's (flag) kept set."""
+    for head_mode in (0, 1):
+        P, Hq, Hkv, d, L, S, W, k = 2, 14, 2, 128, 33001, 3, 70, 400
+        q, K, V = rand_case(92 + head_mode, P, Hq, Hkv, d, L, BF16)
+        G = Hq // Hkv if head_mode else 1
+        Kc, Vc, kept, s = ref.select(BF16, head_mode, q, K, V, S, W, k, want_scores=True)
+        two = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=True, head_mode=head_mode)
+        one = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=True, head_mode=head_mode, flags=1)
+        assert two["redone"] == -1 and one["redone"] == -1
+        for out in (two, one):
+            gu.check_scores(out["scores"].reshape(s.shape), s)
+            for li in range(G):
+                cut = lambda a: np.concatenate([a[..., :S], a[..., S + li * k:S + (li + 1) * k], a[..., S + G * k:]], axis=-1)
+                gu.check_kept(cut(out["kept"]), cut(kept), s[:, :, li], S, W, k)
+        np.testing.assert_array_equal(two["kept"], one["kept"])
+
+
 def test_select_C2_shape_two_layers(ref):
     """Config C2's row shape (32q/8kv, d128, bf16, L 32768, 4+1788+256) on 2 of its 32 layers."""
     cfg = synth.CONFIGS["C2"].with_(n_layers=2)
