@@ -214,6 +214,36 @@ sagekv_status sagekv_decode_step_static(const sagekv_decode_desc* desc, const vo
                                         const void* v_new, void* Kc, void* Vc, int32_t n_appended, float* out,
                                         void* hip_stream);
 
+/* ---- reduced cache in pages ------------------------------------------------------------------
+ * A serving engine keeps its caches in pages, the reduced one too (Sec. 4: the method plugs into
+ * existing inference stacks; Sec. 2 Step 3 only fixes WHICH tokens the reduced cache holds and their
+ * order).  With a sagekv_paged_kv for the reduced cache, Kc and Vc are page pools: a page holds
+ * [n_kv_heads][page_size][head_dim] elements (contiguous), pages are k_stride_page / v_stride_page
+ * elements apart, and token t of a reduced row of problem p, KV head c, sits at
+ *   pool + block_table[p * table_pitch + t / page_size] * stride_page + (c * page_size + t % page_size) * head_dim.
+ * table_pitch >= ceil(compact_capacity / page_size); page_size a power of two >= 16; the pages of
+ * different problems must be distinct.  Everything else is as in the dense calls of the same name. */
+
+/* sagekv_select (in_pages == NULL: K, V strided as in sagekv_select; else pools as in
+ * sagekv_select_paged) gathering into a paged reduced cache. */
+sagekv_status sagekv_select_into_pages(const sagekv_select_desc* desc, const sagekv_paged_kv* in_pages,
+                                       const sagekv_paged_kv* out_pages, const void* q_last, const void* K,
+                                       const void* V, void* Kc_pool, void* Vc_pool, int32_t* kept_idx,
+                                       float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* sagekv_decode_attn over a paged reduced cache. */
+sagekv_status sagekv_decode_attn_paged(const sagekv_decode_desc* desc, const sagekv_paged_kv* pages, const void* q,
+                                       const void* Kc_pool, const void* Vc_pool, int32_t len, float* out,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* sagekv_decode_step over a paged reduced cache: the new token is stored in the page that holds its
+ * ring slot.  ring_state == NULL: `n_appended` counts the appended tokens (as in sagekv_decode_step);
+ * else the count lives on the device (as in sagekv_decode_step_ring) and n_appended is ignored. */
+sagekv_status sagekv_decode_step_paged(const sagekv_decode_desc* desc, const sagekv_paged_kv* pages, const void* q,
+                                       const void* k_new, const void* v_new, void* Kc_pool, void* Vc_pool,
+                                       int32_t n_appended, int32_t* ring_state, float* out, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream);
+
 /* Window-relative rotary positions (the StreamLLM_R cache mode of Sec. 3.1, baseline (3a), App. A.1:
  * the entry at index i of a window of n entries has position i, the query position n-1, so
  * positions stay bounded however long the generation runs).  Rotary attention depends on position

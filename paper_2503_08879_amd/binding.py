@@ -23,6 +23,7 @@ EXPORTS = (
     "sagekv_append",
     "sagekv_decode_workspace_bytes", "sagekv_decode_attn", "sagekv_decode_step", "sagekv_decode_step_ring",
     "sagekv_decode_step_static",
+    "sagekv_select_into_pages", "sagekv_decode_attn_paged", "sagekv_decode_step_paged",
     "sagekv_decode_attn_window", "sagekv_decode_step_window",
     "sagekv_stage_timing_enable", "sagekv_stage_timing_read", "sagekv_stage_timing_stages",
     "sagekv_paper_budget",
@@ -97,6 +98,13 @@ def lib():
         L.sagekv_decode_step.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.sagekv_decode_step_ring.restype = ctypes.c_int
         L.sagekv_decode_step_ring.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        pk = ctypes.POINTER(PagedKV)
+        L.sagekv_select_into_pages.restype = ctypes.c_int
+        L.sagekv_select_into_pages.argtypes = [ctypes.POINTER(SelectDesc), pk, pk, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.sagekv_decode_attn_paged.restype = ctypes.c_int
+        L.sagekv_decode_attn_paged.argtypes = [ctypes.POINTER(DecodeDesc), pk, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.sagekv_decode_step_paged.restype = ctypes.c_int
+        L.sagekv_decode_step_paged.argtypes = [ctypes.POINTER(DecodeDesc), pk, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.sagekv_decode_step_static.restype = ctypes.c_int
         L.sagekv_decode_step_static.argtypes = [ctypes.POINTER(DecodeDesc), vp, vp, vp, vp, vp, i32, vp, vp]
         L.sagekv_decode_attn_window.restype = ctypes.c_int
@@ -245,6 +253,41 @@ def sagekv_decode_step_ring(desc: DecodeDesc, q, k_new, v_new, Kc, Vc, ring_stat
     _check(lib().sagekv_decode_step_ring(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(Kc), _ptr(Vc),
                                          _ptr(ring_state), _ptr(out), _ptr(workspace), _ws_bytes(workspace),
                                          _stream()), "sagekv_decode_step_ring")
+
+
+def compact_pages(block_table, Kc_pool, Vc_pool) -> PagedKV:
+    """Page description of a reduced cache: pools [n_pages, Hkv, page_size, d] (pages contiguous inside,
+    any distance apart), block_table [P, pages_per_row] int32."""
+    import torch
+
+    n_pages, Hkv, page_size, d = Kc_pool.shape
+    assert block_table.dtype == torch.int32 and block_table.stride(1) == 1
+    for pool in (Kc_pool, Vc_pool):
+        assert pool.stride(3) == 1 and pool.stride(2) == d and pool.stride(1) == page_size * d
+    return PagedKV(block_table.data_ptr(), block_table.stride(0), page_size, n_pages, Kc_pool.stride(0), Vc_pool.stride(0))
+
+
+def sagekv_select_into_pages(desc: SelectDesc, in_pages, out_pages: PagedKV, q_last, K, V, Kc_pool, Vc_pool, kept_idx,
+                             scores_out, workspace) -> None:
+    """The eviction pass gathering into a paged reduced cache (in_pages None: K, V strided)."""
+    code = lib().sagekv_select_into_pages(ctypes.byref(desc), None if in_pages is None else ctypes.byref(in_pages),
+                                          ctypes.byref(out_pages), _ptr(q_last), _ptr(K), _ptr(V), _ptr(Kc_pool),
+                                          _ptr(Vc_pool), _ptr(kept_idx), _ptr(scores_out), _ptr(workspace),
+                                          _ws_bytes(workspace), _stream())
+    _check(code, "sagekv_select_into_pages")
+
+
+def sagekv_decode_attn_paged(desc: DecodeDesc, pages: PagedKV, q, Kc_pool, Vc_pool, length: int, out, workspace) -> None:
+    _check(lib().sagekv_decode_attn_paged(ctypes.byref(desc), ctypes.byref(pages), _ptr(q), _ptr(Kc_pool), _ptr(Vc_pool),
+                                          length, _ptr(out), _ptr(workspace), _ws_bytes(workspace), _stream()),
+           "sagekv_decode_attn_paged")
+
+
+def sagekv_decode_step_paged(desc: DecodeDesc, pages: PagedKV, q, k_new, v_new, Kc_pool, Vc_pool, n_appended: int,
+                             ring_state, out, workspace) -> None:
+    _check(lib().sagekv_decode_step_paged(ctypes.byref(desc), ctypes.byref(pages), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                          _ptr(Kc_pool), _ptr(Vc_pool), n_appended, _ptr(ring_state), _ptr(out),
+                                          _ptr(workspace), _ws_bytes(workspace), _stream()), "sagekv_decode_step_paged")
 
 
 STATIC_SCRATCH_BYTES = 4 * 1024 * 1024

@@ -273,6 +273,27 @@ struct StageTimer {
 
 sagekv_status dev(hipError_t e) { return e == hipSuccess ? SAGEKV_OK : SAGEKV_ERR_DEVICE; }
 
+// Checks the page description of a reduced cache of `capacity` tokens per row and turns it into the
+// kernels' page map.
+sagekv_status compact_page_map(const sagekv_paged_kv* pg, int dtype, int n_kv_heads, int head_dim, int64_t capacity,
+                               PageMap* pm) {
+  if (!pg || !pg->block_table || pg->n_pages < 1) return SAGEKV_ERR_INVALID_ARG;
+  const int ps = pg->page_size;
+  if (ps < 16 || (ps & (ps - 1))) return SAGEKV_ERR_INVALID_ARG;
+  if (pg->table_pitch < (capacity + ps - 1) / ps) return SAGEKV_ERR_INVALID_ARG;
+  const int64_t page_elems = (int64_t)n_kv_heads * ps * head_dim;
+  if (pg->k_stride_page < page_elems || pg->v_stride_page < page_elems) return SAGEKV_ERR_INVALID_ARG;
+  const int epl = dtype == SAGEKV_BF16 ? 8 : 4;
+  if ((uintptr_t)pg->block_table & 3u || pg->k_stride_page % epl || pg->v_stride_page % epl) return SAGEKV_ERR_UNSUPPORTED;
+  pm->table = pg->block_table;
+  pm->pitch = pg->table_pitch;
+  pm->ks_page = pg->k_stride_page;
+  pm->vs_page = pg->v_stride_page;
+  pm->shift = __builtin_ctz((unsigned)ps);
+  pm->n_pages = pg->n_pages;
+  return SAGEKV_OK;
+}
+
 // Scratch of sagekv_decode_step_static: the split partials of a decode step, for callers that cannot
 // hand over device memory.  Every GPU the library runs on holds its own copy of this array at its
 // own address; in host code the name is only a handle for hipGetSymbolAddress, never an address.
@@ -305,7 +326,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void* q_sink, const void* k_new,
                          const void* v_new,
                          void* Kc, void* Vc, int slot, int len, int32_t* ring, float* out, void* ws,
-                         size_t ws_bytes, hipStream_t s) {
+                         size_t ws_bytes, hipStream_t s, const PageMap* cpm = nullptr) {
   if (!aligned16(q) || !aligned16(q_sink) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(Kc) ||
       !aligned16(Vc) || ((uintptr_t)out & 3u) || !aligned16(ws) || ((uintptr_t)ring & 3u))
     return SAGEKV_ERR_UNSUPPORTED;
@@ -338,6 +359,7 @@ sagekv_status run_decode(const sagekv_decode_desc* d, const void* q, const void*
   p.ring_W = d->n_recent;
   p.ring_grow = d->grow_recent;
   p.ring_advance = ring != nullptr;
+  if (cpm) p.cpm = *cpm;
   // a reduced cache that cannot stay in L2 / Infinity Cache between steps is streamed (measured: +8 %)
   p.pq_S = d->n_sink;
   p.pq_k = decode_lists(d) > 1 ? d->k : 0;
@@ -392,7 +414,7 @@ namespace {
 
 sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const void* q_last, const void* K,
                           const void* V, void* Kc, void* Vc, int32_t* kept_idx, float* scores_out, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+                          size_t workspace_bytes, void* hip_stream, const PageMap* out_pm = nullptr) {
   sagekv_status st;
   if (!check_select(d, &st)) return st;
   if (!q_last || !K || !V || !Kc || !Vc || !kept_idx) return SAGEKV_ERR_INVALID_ARG;
@@ -651,6 +673,7 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
   gp.Vc = Vc;
   gp.n_kept = d->n_sink + l.n_lists * d->k + d->n_recent;
   gp.cap = d->compact_capacity;
+  if (out_pm) gp.cpm = *out_pm;
   t.begin(SAGEKV_STAGE_GATHER);
   e = launch_gather(gp, s);
   t.end(SAGEKV_STAGE_GATHER);
@@ -668,11 +691,11 @@ sagekv_status sagekv_select(const sagekv_select_desc* d, const void* q_last, con
   return select_impl(d, none, q_last, K, V, Kc, Vc, kept_idx, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
-sagekv_status sagekv_select_paged(const sagekv_select_desc* d, const sagekv_paged_kv* pg, const void* q_last,
-                                  const void* K_pool, const void* V_pool, void* Kc, void* Vc, int32_t* kept_idx,
-                                  float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  sagekv_status st;
-  if (!check_select(d, &st)) return st;
+}  // extern "C"
+
+namespace {
+// Page map of a paged FULL cache (the strides inside a page come from the select descriptor).
+sagekv_status input_page_map(const sagekv_select_desc* d, const sagekv_paged_kv* pg, PageMap* pm) {
   if (!pg || !pg->block_table || pg->n_pages < 1) return SAGEKV_ERR_INVALID_ARG;
   if ((uintptr_t)pg->block_table & 3u) return SAGEKV_ERR_UNSUPPORTED;
   const int ps = pg->page_size;
@@ -681,15 +704,45 @@ sagekv_status sagekv_select_paged(const sagekv_select_desc* d, const sagekv_page
   const int epl = d->dtype == SAGEKV_BF16 ? 8 : 4;
   if (pg->k_stride_page < 0 || pg->v_stride_page < 0 || pg->k_stride_page % epl || pg->v_stride_page % epl)
     return SAGEKV_ERR_UNSUPPORTED;
+  pm->table = pg->block_table;
+  pm->pitch = pg->table_pitch;
+  pm->ks_page = pg->k_stride_page;
+  pm->vs_page = pg->v_stride_page;
+  pm->shift = __builtin_ctz((unsigned)ps);
+  pm->n_pages = pg->n_pages;
+  return SAGEKV_OK;
+}
+}  // namespace
+
+extern "C" {
+
+sagekv_status sagekv_select_paged(const sagekv_select_desc* d, const sagekv_paged_kv* pg, const void* q_last,
+                                  const void* K_pool, const void* V_pool, void* Kc, void* Vc, int32_t* kept_idx,
+                                  float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_select(d, &st)) return st;
   PageMap pm;
-  pm.table = pg->block_table;
-  pm.pitch = pg->table_pitch;
-  pm.ks_page = pg->k_stride_page;
-  pm.vs_page = pg->v_stride_page;
-  pm.shift = __builtin_ctz((unsigned)ps);
-  pm.n_pages = pg->n_pages;
+  st = input_page_map(d, pg, &pm);
+  if (st != SAGEKV_OK) return st;
   return select_impl(d, pm, q_last, K_pool, V_pool, Kc, Vc, kept_idx, scores_out, workspace, workspace_bytes,
                      hip_stream);
+}
+
+sagekv_status sagekv_select_into_pages(const sagekv_select_desc* d, const sagekv_paged_kv* in_pages,
+                                       const sagekv_paged_kv* out_pages, const void* q_last, const void* K,
+                                       const void* V, void* Kc_pool, void* Vc_pool, int32_t* kept_idx,
+                                       float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_select(d, &st)) return st;
+  PageMap in_pm = {nullptr, 0, 0, 0, 0, 0}, out_pm;
+  if (in_pages) {
+    st = input_page_map(d, in_pages, &in_pm);
+    if (st != SAGEKV_OK) return st;
+  }
+  st = compact_page_map(out_pages, d->dtype, d->n_kv_heads, d->head_dim, d->compact_capacity, &out_pm);
+  if (st != SAGEKV_OK) return st;
+  return select_impl(d, in_pm, q_last, K, V, Kc_pool, Vc_pool, kept_idx, scores_out, workspace, workspace_bytes,
+                     hip_stream, &out_pm);
 }
 
 sagekv_status sagekv_select_redone_rows(const sagekv_select_desc* d, const void* workspace, size_t workspace_bytes,
@@ -787,6 +840,43 @@ sagekv_status sagekv_decode_step_static(const sagekv_decode_desc* d, const void*
   if (st != SAGEKV_OK) return st;
   return run_decode(d, q, nullptr, k_new, v_new, Kc, Vc, (int)slot, (int)len, nullptr, out, ws,
                     (size_t)SAGEKV_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
+}
+
+sagekv_status sagekv_decode_attn_paged(const sagekv_decode_desc* d, const sagekv_paged_kv* pages, const void* q,
+                                       const void* Kc_pool, const void* Vc_pool, int32_t len, float* out,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_decode(d, &st)) return st;
+  if (!q || !Kc_pool || !Vc_pool || !out || len < 1 || len > d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
+  PageMap cpm;
+  st = compact_page_map(pages, d->dtype, d->n_kv_heads, d->head_dim, d->compact_capacity, &cpm);
+  if (st != SAGEKV_OK) return st;
+  return run_decode(d, q, nullptr, nullptr, nullptr, const_cast<void*>(Kc_pool), const_cast<void*>(Vc_pool), -1, len,
+                    nullptr, out, workspace, workspace_bytes, (hipStream_t)hip_stream, &cpm);
+}
+
+sagekv_status sagekv_decode_step_paged(const sagekv_decode_desc* d, const sagekv_paged_kv* pages, const void* q,
+                                       const void* k_new, const void* v_new, void* Kc_pool, void* Vc_pool,
+                                       int32_t n_appended, int32_t* ring_state, float* out, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  sagekv_status st;
+  if (!check_decode(d, &st)) return st;
+  if (!q || !k_new || !v_new || !Kc_pool || !Vc_pool || !out || (!ring_state && n_appended < 0))
+    return SAGEKV_ERR_INVALID_ARG;
+  PageMap cpm;
+  st = compact_page_map(pages, d->dtype, d->n_kv_heads, d->head_dim, d->compact_capacity, &cpm);
+  if (st != SAGEKV_OK) return st;
+  const int base = d->n_sink + decode_lists(d) * d->k;
+  if (ring_state) {
+    const int len = d->grow_recent ? d->compact_capacity : base + d->n_recent;
+    return run_decode(d, q, nullptr, k_new, v_new, Kc_pool, Vc_pool, 0, len, ring_state, out, workspace,
+                      workspace_bytes, (hipStream_t)hip_stream, &cpm);
+  }
+  const int64_t slot = d->grow_recent ? (int64_t)base + d->n_recent + n_appended : base + n_appended % d->n_recent;
+  const int64_t len = d->grow_recent ? slot + 1 : (int64_t)base + d->n_recent;
+  if (slot >= d->compact_capacity) return SAGEKV_ERR_INVALID_ARG;
+  return run_decode(d, q, nullptr, k_new, v_new, Kc_pool, Vc_pool, (int)slot, (int)len, nullptr, out, workspace,
+                    workspace_bytes, (hipStream_t)hip_stream, &cpm);
 }
 
 sagekv_status sagekv_decode_step_ring(const sagekv_decode_desc* d, const void* q, const void* k_new, const void* v_new,

@@ -115,8 +115,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tq = lane / LPT, cl = lane % LPT;
 
-  char* Kr = (char*)p.Kc + (int64_t)row * p.cap * ROWB;
-  char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
+  const CacheRow Kr = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, EB);
+  const CacheRow Vr = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, EB);
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
   const StepGeom sg = step_geom(p);
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
   const int t_end = min(sg.len, t_begin + sg.tokens_per_split);
 
   if (slot >= t_begin && slot < t_end && tid < LPT) {  // Step 4: the new token enters the window
-    st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
-    st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
+    st16(Kr.at(slot) + tid * 16, ld16(kn + tid * 16));
+    st16(Vr.at(slot) + tid * 16, ld16(vn + tid * 16));
   }
 
   uint4 q[GB], q2[GB];  // q2: the sink tokens' query (window-relative positions), else = q
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
       const int tok = t0 + i * TPL + tq;
       valid[i] = tok < t_end;
       const int tc = valid[i] ? tok : t_begin;
-      const char* ks = (tc == slot) ? kn : Kr + (int64_t)tc * ROWB;
-      const char* vs = (tc == slot) ? vn : Vr + (int64_t)tc * ROWB;
+      const char* ks = (tc == slot) ? kn : Kr.at(tc);
+      const char* vs = (tc == slot) ? vn : Vr.at(tc);
       kv[i] = ld16(ks + cl * 16);
       vv[i] = ld16(vs + cl * 16);
     }
@@ -278,8 +278,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   const int tq = lane / CH, cl = lane % CH;  // load / PV role: token sub-index, 16-byte chunk
   const int n = lane & 15, j = lane >> 4;    // MFMA role: column (token), row block
 
-  char* Kr = (char*)p.Kc + (int64_t)row * p.cap * ROWB;
-  char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
+  const CacheRow Kr = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, 2);
+  const CacheRow Vr = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, 2);
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
   const StepGeom sg = step_geom(p);
@@ -287,8 +287,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   const int t_begin = split * sg.tokens_per_split;
   const int t_end = min(sg.len, t_begin + sg.tokens_per_split);
   if (slot >= t_begin && slot < t_end && tid < CH) {  // Step 4: the new token enters the window
-    st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
-    st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
+    st16(Kr.at(slot) + tid * 16, ld16(kn + tid * 16));
+    st16(Vr.at(slot) + tid * 16, ld16(vn + tid * 16));
   }
 
   // accumulator rows 4j..4j+3 = (tile slot, heads hbase..hbase+3); slots >= NT stay empty
@@ -309,12 +309,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   uint4* buf = kbuf[wave];
   const int nblk = (t_end - t_begin + BT - 1) / BT;
   uint4 kv[NLOAD], vv[NLOAD];
-  auto load_block = [&](int b, uint4* dst, const char* base, const char* fresh) {
+  auto load_block = [&](int b, uint4* dst, const CacheRow& base, const char* fresh) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int tok = t_begin + b * BT + i * TPL + tq;
       const int tc = tok < t_end ? tok : t_begin;
-      const char* src = (tc == slot) ? fresh : base + (int64_t)tc * ROWB;
+      const char* src = (tc == slot) ? fresh : base.at(tc);
       dst[i] = STREAM ? ld16_stream(src + cl * 16) : ld16(src + cl * 16);
     }
   };
@@ -414,7 +414,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
       if (more) {  // the register is free: V of the next block, as early as possible
         const int tokn = t_begin + (b + NW) * BT + i * TPL + tq;
         const int tcn = tokn < t_end ? tokn : t_begin;
-        const char* src = (tcn == slot) ? vn : Vr + (int64_t)tcn * ROWB;
+        const char* src = (tcn == slot) ? vn : Vr.at(tcn);
         vv[i] = STREAM ? ld16_stream(src + cl * 16) : ld16(src + cl * 16);
       }
 #pragma unroll
@@ -515,8 +515,8 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   const int tq = lane / CH, cl = lane % CH;  // load role: token sub-index, 16-byte chunk
   const int n = lane & 15, j = lane >> 4;    // MFMA role: column, row block / k-group
 
-  char* Kr = (char*)p.Kc + (int64_t)row * p.cap * ROWB;
-  char* Vr = (char*)p.Vc + (int64_t)row * p.cap * ROWB;
+  const CacheRow Kr = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, 2);
+  const CacheRow Vr = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, 2);
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
   const StepGeom sg = step_geom(p);
@@ -524,8 +524,8 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   const int t_begin = split * sg.tokens_per_split;
   const int t_end = min(sg.len, t_begin + sg.tokens_per_split);
   if (slot >= t_begin && slot < t_end && tid < CH) {  // Step 4: the new token enters the window
-    st16(Kr + (int64_t)slot * ROWB + tid * 16, ld16(kn + tid * 16));
-    st16(Vr + (int64_t)slot * ROWB + tid * 16, ld16(vn + tid * 16));
+    st16(Kr.at(slot) + tid * 16, ld16(kn + tid * 16));
+    st16(Vr.at(slot) + tid * 16, ld16(vn + tid * 16));
   }
 
   // q.K accumulator a, register r of lane (j, n): head hbase + r, token tile a * TILES + tslot, column n
@@ -544,12 +544,12 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   reinterpret_cast<uint4*>(&pT[wave][0][0])[lane] = make_uint4(0u, 0u, 0u, 0u);  // rows of absent heads stay 0
   const int nblk = (t_end - t_begin + BT - 1) / BT;
   uint4 kv[NLOAD], vv[NLOAD];
-  auto load_block = [&](int b, uint4* dst, const char* base, const char* fresh) {
+  auto load_block = [&](int b, uint4* dst, const CacheRow& base, const char* fresh) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int tok = t_begin + b * BT + i * TPL + tq;
       const int tc = tok < t_end ? tok : t_begin;
-      const char* src = (tc == slot) ? fresh : base + (int64_t)tc * ROWB;
+      const char* src = (tc == slot) ? fresh : base.at(tc);
       dst[i] = STREAM ? ld16_stream(src + cl * 16) : ld16(src + cl * 16);
     }
   };
@@ -729,10 +729,11 @@ template <int LPT>
 __global__ __launch_bounds__(64) void append_kernel(DecodeParams p, int row_bytes) {
   const int row = blockIdx.x, tid = threadIdx.x;
   if (tid >= LPT) return;
-  char* Kr = (char*)p.Kc + ((int64_t)row * p.cap + p.slot) * row_bytes;
-  char* Vr = (char*)p.Vc + ((int64_t)row * p.cap + p.slot) * row_bytes;
-  st16(Kr + tid * 16, ld16((const char*)p.k_new + (int64_t)row * row_bytes + tid * 16));
-  st16(Vr + tid * 16, ld16((const char*)p.v_new + (int64_t)row * row_bytes + tid * 16));
+  const int prob = row / p.Hkv, c = row % p.Hkv, eb = row_bytes / p.D;
+  const CacheRow Kr = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, row_bytes, eb);
+  const CacheRow Vr = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, row_bytes, eb);
+  st16(Kr.at(p.slot) + tid * 16, ld16((const char*)p.k_new + (int64_t)row * row_bytes + tid * 16));
+  st16(Vr.at(p.slot) + tid * 16, ld16((const char*)p.v_new + (int64_t)row * row_bytes + tid * 16));
 }
 
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {

@@ -49,6 +49,39 @@ __device__ __forceinline__ int64_t kv_offset(const PageMap& pm, int64_t s_page, 
   return (int64_t)page_of(pm, prob, tok) * s_page + (int64_t)c * s_head + (tok & ((1 << pm.shift) - 1)) * s_token;
 }
 
+// One row of the reduced cache, K or V: dense [cap][D] elements, or spread over pages of a pool (a
+// page holds [Hkv][2^shift][D] elements).  at(t) = address of logical token t of the row.
+struct CacheRow {
+  char* base;          // dense: the row's first token; paged: the pool, advanced to the row's KV head
+  const int32_t* tab;  // paged: the problem's row of the block table, else null
+  int64_t page_bytes;
+  int shift, n_pages, rowb;
+  __device__ __forceinline__ char* at(int tok) const {
+    if (!tab) return base + (int64_t)tok * rowb;
+    int pid = tab[tok >> shift];
+    pid = pid < 0 ? 0 : (pid >= n_pages ? n_pages - 1 : pid);
+    return base + (int64_t)pid * page_bytes + (int64_t)(tok & ((1 << shift) - 1)) * rowb;
+  }
+};
+__device__ __forceinline__ CacheRow cache_row(void* cache, const PageMap& cpm, bool v, int prob, int c, int row, int cap,
+                                              int rowb, int eb /* bytes per element */) {
+  CacheRow r;
+  r.rowb = rowb;
+  if (!cpm.table) {
+    r.base = (char*)cache + (int64_t)row * cap * rowb;
+    r.tab = nullptr;
+    r.page_bytes = 0;
+    r.shift = r.n_pages = 0;
+  } else {
+    r.base = (char*)cache + ((int64_t)c << cpm.shift) * rowb;
+    r.tab = cpm.table + (int64_t)prob * cpm.pitch;
+    r.page_bytes = (v ? cpm.vs_page : cpm.ks_page) * (int64_t)eb;
+    r.shift = cpm.shift;
+    r.n_pages = cpm.n_pages;
+  }
+  return r;
+}
+
 // Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy of
 // the kernel).  `done`: one bit per device, file-scope state of the caller.  Two host threads racing
 // here at worst set the attribute twice.
@@ -241,6 +274,7 @@ struct GatherParams {
   void* Kc;
   void* Vc;
   int n_kept, cap;
+  PageMap cpm;  // reduced cache in pages (see DecodeParams), table = null: dense rows of `cap` tokens
 };
 
 struct DecodeParams {
@@ -265,6 +299,9 @@ struct DecodeParams {
   // per-query head mode: rows are [sink | list of head 0 | ... | list of head G-1 | recent]; head g
   // attends the sink, its own list and the recent window.  pq_k = 0: every head attends everything.
   int pq_S, pq_k;
+  // Reduced cache in pages (cpm.table != null): Kc / Vc are page pools, a page holds [Hkv][2^shift][D]
+  // elements and logical token t of problem p sits in page cpm.table[p * cpm.pitch + (t >> shift)].
+  PageMap cpm;
   float* part_acc;     // [rows][n_splits][G][D]
   float2* part_ml;     // [rows][n_splits][G]   (max, sum)
   float* out;          // [P][Hq][D]

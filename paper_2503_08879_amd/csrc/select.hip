@@ -418,8 +418,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
   const int sub = threadIdx.x / LPT, cl = threadIdx.x % LPT;
   constexpr int TPI = kGatherThreads / LPT;  // tokens per iteration
   const int64_t row_bytes = (int64_t)p.geo.D * eb;
-  char* Kc = (char*)p.Kc + (int64_t)row * p.cap * row_bytes;
-  char* Vc = (char*)p.Vc + (int64_t)row * p.cap * row_bytes;
+  const CacheRow Kc = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, (int)row_bytes, eb);
+  const CacheRow Vc = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, (int)row_bytes, eb);
   const int32_t* kept = p.kept_idx + (int64_t)row * p.n_kept;
   const int t0 = blockIdx.x * kGatherTokens;
   constexpr int NIT = kGatherTokens / TPI;
@@ -444,8 +444,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherParams p, 
   for (int it = 0; it < NIT; ++it) {
     const int t = t0 + it * TPI + sub;
     if (t < p.n_kept) {
-      st16(Kc + t * row_bytes + cl * 16, a[it]);
-      st16(Vc + t * row_bytes + cl * 16, b[it]);
+      st16(Kc.at(t) + cl * 16, a[it]);
+      st16(Vc.at(t) + cl * 16, b[it]);
     }
   }
 }

@@ -20,7 +20,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert "sagekv_select" in names and "sagekv_decode_attn" in names and len(names) == 17
+    assert "sagekv_select" in names and "sagekv_decode_attn" in names and len(names) == 20
     lib = ctypes.CDLL(sk.binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
