@@ -49,57 +49,70 @@ def read_traffic(cfg_name, key="traffic_bytes_per_launch"):
 
 
 def cpu_model():
+    """Model string of the host CPU; virtual machines often shorten the name, so family / model /
+    stepping and the CPU counts go with it."""
+    info = {}
     try:
         for line in open("/proc/cpuinfo"):
-            if line.startswith("model name"):
-                return line.split(":", 1)[1].strip()
+            if ":" in line:
+                k, v = (x.strip() for x in line.split(":", 1))
+                if k in ("model name", "vendor_id", "cpu family", "model", "stepping") and k not in info:
+                    info[k] = v
     except OSError:
         pass
-    return "unknown"
+    name = info.get("model name", "unknown")
+    extra = ", ".join(f"{k} {info[k]}" for k in ("vendor_id", "cpu family", "model", "stepping") if k in info)
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    return f"{name} ({extra}; {os.cpu_count()} logical CPUs, {usable} usable by this process)"
 
 
-def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
-    """Times the CPU oracle, as it stands, on the first n_layers layers of the same workload: the
-    eviction pass repeated for about select_seconds, then decode steps for about decode_seconds."""
+def cpu_baseline(cfg, K_dev, V_dev, select_repeats, decode_seconds):
+    """Times the CPU oracle, as it stands, on the WHOLE workload: the eviction pass over every layer
+    (K and V of one layer at a time are copied from the device, which holds the bench's own inputs;
+    the copies are not timed), `select_repeats` times, then decode steps over all layers for about
+    decode_seconds.  Returns the baseline record and the oracle's kept indices of every row."""
     import numpy as np
 
     import synth
     from oracle import ref
 
-    n_layers = min(n_layers, cfg.n_layers)
-    sub = cfg.with_(n_layers=n_layers)
-    q = synth.q_last_host(cfg)[: sub.n_problems].copy()
-    pos, nrows = synth.needles(sub, q)
-    shp = (sub.n_problems, sub.n_kv_heads, sub.L, sub.head_dim)
-    K = np.stack([synth.kv_row_host(sub, "K", r, pos, nrows) for r in range(sub.rows)]).reshape(shp)
-    V = np.stack([synth.kv_row_host(sub, "V", r) for r in range(sub.rows)]).reshape(shp)
-    t_sel, n_sel = 0.0, 0
-    while t_sel < select_seconds:
-        t0 = time.perf_counter()
-        Kc, Vc, kept = ref.select(sub.dtype, ref.GROUP_SUM, q, K, V, sub.n_sink, sub.n_recent, sub.k)
-        t_sel += time.perf_counter() - t0
-        n_sel += 1
+    q = synth.q_last_host(cfg)
+    P = cfg.n_problems
+    t_sel = 0.0
+    Kc_all, Vc_all, kept_all = [], [], []
+    t_one = None
+    for p in range(P):
+        Kp, Vp = synth.torch_to_host(K_dev[p:p + 1], cfg.dtype), synth.torch_to_host(V_dev[p:p + 1], cfg.dtype)
+        qp = np.ascontiguousarray(q[p:p + 1])
+        for _ in range(select_repeats):
+            t0 = time.perf_counter()
+            Kc, Vc, kept = ref.select(cfg.dtype, ref.GROUP_SUM, qp, Kp, Vp, cfg.n_sink, cfg.n_recent, cfg.k)
+            t_sel += time.perf_counter() - t0
+        if p == 0:  # one row = one oracle thread (its only parallel loop is over rows)
+            K1, V1 = np.ascontiguousarray(Kp[:, :1]), np.ascontiguousarray(Vp[:, :1])
+            q1 = np.ascontiguousarray(qp[:, : cfg.G])
+            t0 = time.perf_counter()
+            ref.select(cfg.dtype, ref.GROUP_SUM, q1, K1, V1, cfg.n_sink, cfg.n_recent, cfg.k)
+            t_one = time.perf_counter() - t0
+        Kc_all.append(Kc), Vc_all.append(Vc), kept_all.append(kept)
+        del Kp, Vp
+    t_pass = t_sel / select_repeats
+    Kc, Vc, kept = np.concatenate(Kc_all), np.concatenate(Vc_all), np.concatenate(kept_all)
     t_dec, n_dec = 0.0, 0
     while t_dec < decode_seconds:
         qs, kn, vn = synth.decode_inputs_host(cfg, n_dec % max(cfg.decode_steps, 1))
-        qs, kn, vn = (np.ascontiguousarray(x[: sub.n_problems]) for x in (qs, kn, vn))
         t0 = time.perf_counter()
-        ref.append(sub.dtype, Kc, Vc, kn, vn, sub.n_sink + sub.k, sub.n_recent)
-        ref.decode_attn(sub.dtype, ref.GROUP_SUM, qs, Kc, Vc, sub.budget)
+        ref.append(cfg.dtype, Kc, Vc, kn, vn, cfg.n_sink + cfg.k, cfg.n_recent)
+        ref.decode_attn(cfg.dtype, ref.GROUP_SUM, qs, Kc, Vc, cfg.budget)
         t_dec += time.perf_counter() - t0
         n_dec += 1
-    # one row = one oracle thread (its only parallel loop is over rows)
-    one = sub.with_(n_layers=1, batch=1)
-    K1 = np.ascontiguousarray(K[:1, :1])
-    V1 = np.ascontiguousarray(V[:1, :1])
-    q1 = np.ascontiguousarray(q[:1, : sub.G])
-    t0 = time.perf_counter()
-    ref.select(sub.dtype, ref.GROUP_SUM, q1, K1, V1, sub.n_sink, sub.n_recent, sub.k)
-    t_one = time.perf_counter() - t0
-    one_row_bytes = algorithmic_bytes(one)[0] // one.n_kv_heads
-    sel_b, dec_b, _ = algorithmic_bytes(sub)
+    one_row_bytes = algorithmic_bytes(cfg)[0] // cfg.rows
+    sel_b, dec_b, _ = algorithmic_bytes(cfg)
     # same mix as a bench step: one eviction pass + cfg.decode_steps decode steps
-    t_step = t_sel / n_sel + cfg.decode_steps * t_dec / n_dec
+    t_step = t_pass + cfg.decode_steps * t_dec / n_dec
     return {
         "value": (sel_b + cfg.decode_steps * dec_b) / t_step / 1e9,
         "unit": "GB/s",
@@ -107,12 +120,12 @@ def cpu_baseline(cfg, n_layers, select_seconds, decode_seconds):
         "kind": "oracle",
         "cpu_model": cpu_model(),
         "select_GBps_one_thread": one_row_bytes / t_one / 1e9,
-        "sample": f"first {n_layers} of {cfg.n_layers} layers ({sub.rows} rows of L={cfg.L}): eviction pass x{n_sel} "
-                  f"({t_sel:.1f} s), {n_dec} decode steps ({t_dec:.1f} s); value = bytes of (1 pass + "
-                  f"{cfg.decode_steps} steps) on these layers / their time",
-        "select_GBps": sel_b / (t_sel / n_sel) / 1e9,
-        "select_ms_all_layers": t_sel / n_sel * 1e3 * cfg.n_layers / n_layers,
-        "decode_tokens_per_s": cfg.batch / (t_dec / n_dec) * n_layers / cfg.n_layers,
+        "sample": f"the whole workload: the eviction pass over all {cfg.n_layers} layers ({cfg.rows} rows of L={cfg.L}) "
+                  f"x{select_repeats} ({t_sel:.1f} s), then {n_dec} decode steps over all layers ({t_dec:.1f} s); value = "
+                  f"bytes of (1 pass + {cfg.decode_steps} steps) / (pass time + {cfg.decode_steps} x step time)",
+        "select_GBps": sel_b / t_pass / 1e9,
+        "select_ms_all_layers": t_pass * 1e3,
+        "decode_tokens_per_s": cfg.batch / (t_dec / n_dec),
     }, kept
 
 
@@ -220,8 +233,8 @@ def main():
                          "known size for rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--layer-sequential-steps", type=int, default=8,
                     help="decode steps of the untimed-in-value extra figure that launches one layer at a time")
-    ap.add_argument("--cpu-layers", type=int, default=2)
-    ap.add_argument("--cpu-select-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-select-repeats", type=int, default=3,
+                    help="how often the oracle's eviction pass over the whole workload is timed (about 1-2 s each at C3)")
     ap.add_argument("--cpu-decode-seconds", type=float, default=5.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -402,14 +415,17 @@ def main():
     score_roof = {"kernel": "score_mfma_kernel (the one pass over K of the eviction pass)", "bound": "hbm",
                   "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                   "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(score_ms, 4),
-                  "algorithmic_bytes": score_b, "traffic": None if pages is not None else read_traffic(cfg.name)}
+                  "algorithmic_bytes": score_b, "traffic": None if pages is not None else read_traffic(cfg.name),
+                  "traffic_from": f"profiles/hbm_traffic_{cfg.name}_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                  "command, scaled by a 1 GiB copy; read from the committed summary, not measured in this run)"}
     roofs = [score_roof]
     if n_dec:
         dec_roof = {"kernel": "decode kernel (one launch = append + attention over all rows)", "bound": "hbm",
                     "achieved": round(dec_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(dec_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(dec_ms / n_dec, 5),
                     "algorithmic_bytes": dec_b,
-                    "traffic": read_traffic(cfg.name, "decode_traffic_bytes_per_launch") if lists == 1 else None}
+                    "traffic": read_traffic(cfg.name, "decode_traffic_bytes_per_launch") if lists == 1 else None,
+                    "traffic_from": score_roof["traffic_from"]}
         roofs.append(dec_roof)
     # the kernel the step spends most of its time in
     result["roofline"] = max(roofs, key=lambda r: r["avg_ms"] * (n_dec if r is not score_roof else 1))
@@ -421,8 +437,8 @@ def main():
         result["decode"]["layer_sequential"] = layer_sequential(
             sk, torch, cfg, head_mode, Bt, q_steps, kn_steps, vn_steps, Kc, Vc, out,
             min(n_dec, args.layer_sequential_steps))
-    if not args.no_cpu_baseline:
-        base, kept_ref = cpu_baseline(cfg, args.cpu_layers, args.cpu_select_seconds, args.cpu_decode_seconds)
+    if not args.no_cpu_baseline and pages is None:
+        base, kept_ref = cpu_baseline(cfg, K, V, args.cpu_select_repeats, args.cpu_decode_seconds)
         # free check: the sampled layers' kept sets must be the oracle's
         one_step()
         torch.cuda.synchronize()

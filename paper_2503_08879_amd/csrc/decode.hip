@@ -257,7 +257,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
 // chunks (16 lanes per token, fp32 FMA accumulation).  K and V of block b+1 are both in flight
 // while block b is processed (two 8-load register buffers per wave).  STREAM: the reduced cache
 // does not fit the on-chip caches between steps, read it with streaming loads.
-template <int D, int GPAD, int NW, bool STREAM>
+template <int D, int GPAD, int NW, bool STREAM, bool PG>
 __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, int g0, int gb) {
   constexpr int BT = GPAD > 4 ? 16 : 32;                   // tokens per block (registers: acc is GPAD x 8)
   constexpr int CH = D / 8, TPL = 64 / CH, NLOAD = BT / TPL, KSTEPS = D / 32;
@@ -278,8 +278,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   const int tq = lane / CH, cl = lane % CH;  // load / PV role: token sub-index, 16-byte chunk
   const int n = lane & 15, j = lane >> 4;    // MFMA role: column (token), row block
 
-  const CacheRow Kr = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, 2);
-  const CacheRow Vr = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, 2);
+  const CacheRowT<PG, ROWB> Kr = {cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, 2)};
+  const CacheRowT<PG, ROWB> Vr = {cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, 2)};
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
   const StepGeom sg = step_geom(p);
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p, in
   uint4* buf = kbuf[wave];
   const int nblk = (t_end - t_begin + BT - 1) / BT;
   uint4 kv[NLOAD], vv[NLOAD];
-  auto load_block = [&](int b, uint4* dst, const CacheRow& base, const char* fresh) {
+  auto load_block = [&](int b, uint4* dst, const CacheRowT<PG, ROWB>& base, const char* fresh) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int tok = t_begin + b * BT + i * TPL + tq;
@@ -492,7 +492,7 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {  // finite, non-negative
   return u >> 16;
 }
 
-template <int D, int GPAD, int NW, bool STREAM>
+template <int D, int GPAD, int NW, bool STREAM, bool PG>
 __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p, int g0, int gb) {
   constexpr int BT = 32;
   constexpr int CH = D / 8, TPL = 64 / CH, NLOAD = BT / TPL, KSTEPS = D / 32;
@@ -515,8 +515,8 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   const int tq = lane / CH, cl = lane % CH;  // load role: token sub-index, 16-byte chunk
   const int n = lane & 15, j = lane >> 4;    // MFMA role: column, row block / k-group
 
-  const CacheRow Kr = cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, 2);
-  const CacheRow Vr = cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, 2);
+  const CacheRowT<PG, ROWB> Kr = {cache_row(p.Kc, p.cpm, false, prob, c, row, p.cap, ROWB, 2)};
+  const CacheRowT<PG, ROWB> Vr = {cache_row(p.Vc, p.cpm, true, prob, c, row, p.cap, ROWB, 2)};
   const char* kn = p.k_new ? (const char*)p.k_new + (int64_t)row * ROWB : nullptr;
   const char* vn = p.v_new ? (const char*)p.v_new + (int64_t)row * ROWB : nullptr;
   const StepGeom sg = step_geom(p);
@@ -544,7 +544,7 @@ __global__ __launch_bounds__(NW * 64) void decode_pv_mfma_kernel(DecodeParams p,
   reinterpret_cast<uint4*>(&pT[wave][0][0])[lane] = make_uint4(0u, 0u, 0u, 0u);  // rows of absent heads stay 0
   const int nblk = (t_end - t_begin + BT - 1) / BT;
   uint4 kv[NLOAD], vv[NLOAD];
-  auto load_block = [&](int b, uint4* dst, const CacheRow& base, const char* fresh) {
+  auto load_block = [&](int b, uint4* dst, const CacheRowT<PG, ROWB>& base, const char* fresh) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int tok = t_begin + b * BT + i * TPL + tq;
@@ -762,7 +762,7 @@ hipError_t launch_decode_g(const DecodeParams& p, int g0, int gb, dim3 grid, hip
   return hipGetLastError();
 }
 
-template <int D, bool STREAM>
+template <int D, bool STREAM, bool PG>
 hipError_t launch_decode_mfma_s(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
   // One workgroup per row (many rows): 8 waves, one workgroup per CU; a row split over several
   // workgroups: 4 waves.  (For 256 < rows <= 512, 4-wave workgroups that are all resident at once
@@ -775,22 +775,25 @@ hipError_t launch_decode_mfma_s(const DecodeParams& p, int g0, int gb, dim3 grid
   // (measured 43 vs 47 us at 448 rows x 1024 tokens x 7 heads)
   const bool wide = big && grid.y <= 256;
   if (gb <= 4) {
-    if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
-    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 4, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+    if (big) hipLaunchKernelGGL((decode_mfma_kernel<D, 4, 8, STREAM, PG>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 4, 4, STREAM, PG>), grid, dim3(256), 0, s, p, g0, gb);
   } else if (gb <= 8) {
-    if (wide) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
-    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+    if (wide) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 8, STREAM, PG>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 8, 4, STREAM, PG>), grid, dim3(256), 0, s, p, g0, gb);
   } else {
-    if (wide) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 8, STREAM>), grid, dim3(512), 0, s, p, g0, gb);
-    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 4, STREAM>), grid, dim3(256), 0, s, p, g0, gb);
+    if (wide) hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 8, STREAM, PG>), grid, dim3(512), 0, s, p, g0, gb);
+    else hipLaunchKernelGGL((decode_pv_mfma_kernel<D, 16, 4, STREAM, PG>), grid, dim3(256), 0, s, p, g0, gb);
   }
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_decode_mfma(const DecodeParams& p, int g0, int gb, dim3 grid, hipStream_t s) {
-  return p.stream_loads ? launch_decode_mfma_s<D, true>(p, g0, gb, grid, s)
-                        : launch_decode_mfma_s<D, false>(p, g0, gb, grid, s);
+  if (p.cpm.table)
+    return p.stream_loads ? launch_decode_mfma_s<D, true, true>(p, g0, gb, grid, s)
+                          : launch_decode_mfma_s<D, false, true>(p, g0, gb, grid, s);
+  return p.stream_loads ? launch_decode_mfma_s<D, true, false>(p, g0, gb, grid, s)
+                        : launch_decode_mfma_s<D, false, false>(p, g0, gb, grid, s);
 }
 
 }  // namespace

@@ -63,6 +63,18 @@ struct CacheRow {
     return base + (int64_t)pid * page_bytes + (int64_t)(tok & ((1 << shift) - 1)) * rowb;
   }
 };
+// The same with the layout fixed at compile time (the bf16 decode kernels: a run-time choice in
+// their load addresses costs them 9 % at 256 rows x 4096 tokens).
+template <bool PAGED, int ROWB>
+struct CacheRowT {
+  CacheRow r;
+  __device__ __forceinline__ char* at(int tok) const {
+    if (!PAGED) return r.base + (int64_t)tok * ROWB;
+    int pid = r.tab[tok >> r.shift];
+    pid = pid < 0 ? 0 : (pid >= r.n_pages ? r.n_pages - 1 : pid);
+    return r.base + (int64_t)pid * r.page_bytes + (int64_t)(tok & ((1 << r.shift) - 1)) * ROWB;
+  }
+};
 __device__ __forceinline__ CacheRow cache_row(void* cache, const PageMap& cpm, bool v, int prob, int c, int row, int cap,
                                               int rowb, int eb /* bytes per element */) {
   CacheRow r;
