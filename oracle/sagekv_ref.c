@@ -108,6 +108,7 @@ int sagekv_ref_scores(int dtype, int head_mode, int P, int Hq, int Hkv, int d, i
     double* tmp = (double*)malloc(sizeof(double) * L);
     double* sum = (double*)malloc(sizeof(double) * L);
     if (!tmp || !sum) {
+#pragma omp atomic write
       err = 2;
     } else {
       head_scores(dtype, head_mode, Hq, Hkv, d, L, q_last, K, r / Hkv, r % Hkv, s_out + (int64_t)r * n_lists * L, tmp,
@@ -176,6 +177,7 @@ int sagekv_ref_select(int dtype, int head_mode, int P, int Hq, int Hkv, int d, i
     double* sum = (double*)malloc(sizeof(double) * L);
     cand_t* scratch = (cand_t*)malloc(sizeof(cand_t) * (size_t)(L > 0 ? L : 1));
     if (!s || !tmp || !sum || !scratch) {
+#pragma omp atomic write
       err = 2;
     } else {
       head_scores(dtype, head_mode, Hq, Hkv, d, L, q_last, K, r / Hkv, r % Hkv, s, tmp, sum);
@@ -264,6 +266,7 @@ int sagekv_ref_decode_attn(int dtype, int head_mode, int P, int Hq, int Hkv, int
     int32_t* pos = (int32_t*)malloc(sizeof(int32_t) * n);
     double* w = (double*)malloc(sizeof(double) * n);
     if (!pos || !w) {
+#pragma omp atomic write
       err = 2;
     } else {
       if (head_mode == REF_GROUP_SUM) {
@@ -306,6 +309,7 @@ int sagekv_ref_decode_attn_window_rope(int dtype, int P, int Hq, int Hkv, int d,
     double* qr = (double*)malloc(sizeof(double) * d);
     double* w = (double*)malloc(sizeof(double) * len);
     if (!qr || !w) {
+#pragma omp atomic write
       err = 2;
     } else {
       double pq = (double)(len - 1);
