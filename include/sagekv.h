@@ -21,6 +21,8 @@
  *     positions [n_sink, L - n_recent).
  *   - Errors are return codes.  Arguments are checked before anything is launched:
  *     on SAGEKV_ERR_INVALID_ARG / _UNSUPPORTED / _WORKSPACE nothing was written.
+ *   - One call handles at most 65535 rows (n_problems * n_kv_heads; times G in PER_QUERY selection):
+ *     more is SAGEKV_ERR_UNSUPPORTED, split the problems over several calls.
  *   - Element types: bf16 (raw 16-bit patterns) or fp32; head_dim 64 or 128; the
  *     innermost (head_dim) stride is 1 and rows must be 16-byte aligned: base pointers of
  *     caches, queries and workspaces on 16 bytes (else SAGEKV_ERR_UNSUPPORTED), strides in

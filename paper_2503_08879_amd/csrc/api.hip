@@ -113,12 +113,13 @@ bool check_select(const sagekv_select_desc* d, sagekv_status* st) {
   if (d->head_mode != SAGEKV_HEADS_GROUP_SUM && d->head_mode != SAGEKV_HEADS_PER_QUERY) return false;
   const int64_t lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? d->n_q_heads / d->n_kv_heads : 1;
   if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + lists * d->k) return false;
-  if ((int64_t)d->n_problems * d->n_kv_heads * lists > 65535) return false;
   if (d->flags & ~(uint32_t)SAGEKV_SELECT_DENSE) return false;
   *st = SAGEKV_ERR_UNSUPPORTED;
   if (d->dtype != SAGEKV_BF16 && d->dtype != SAGEKV_F32) return false;
   if (d->head_dim != 64 && d->head_dim != 128) return false;
   if (d->n_q_heads / d->n_kv_heads > 64) return false;
+  // rows (and selection lists) index one grid dimension of the launches
+  if ((int64_t)d->n_problems * d->n_kv_heads * lists > 65535) return false;
   const int epl = d->dtype == SAGEKV_BF16 ? 8 : 4;  // 16-byte alignment of every token row
   const int64_t strides[6] = {d->k_stride_problem, d->k_stride_head, d->k_stride_token,
                               d->v_stride_problem, d->v_stride_head, d->v_stride_token};
@@ -197,8 +198,8 @@ bool check_decode(const sagekv_decode_desc* d, sagekv_status* st) {
   if (d->n_sink < 0 || d->n_recent < 1 || d->k < 0) return false;
   if (d->head_mode != SAGEKV_HEADS_GROUP_SUM && d->head_mode != SAGEKV_HEADS_PER_QUERY) return false;
   if ((int64_t)d->compact_capacity < (int64_t)d->n_sink + d->n_recent + (int64_t)decode_lists(d) * d->k) return false;
-  if ((int64_t)d->n_problems * d->n_kv_heads > 65535) return false;
   *st = SAGEKV_ERR_UNSUPPORTED;
+  if ((int64_t)d->n_problems * d->n_kv_heads > 65535) return false;  // rows index one grid dimension
   if (d->dtype != SAGEKV_BF16 && d->dtype != SAGEKV_F32) return false;
   if (d->head_dim != 64 && d->head_dim != 128) return false;
   *st = SAGEKV_OK;

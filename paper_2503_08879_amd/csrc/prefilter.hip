@@ -217,7 +217,7 @@ __device__ __forceinline__ void flag_row(const TopkCandParams& p, int row, int r
 
 // PQ: per-query lists (n_lists = G > 1), each list keeps its own compacted candidates.
 template <int DT, bool PQ>
-__global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams p) {
+__device__ __forceinline__ void topk_cand_body(const TopkCandParams& p) {
   __shared__ TopkShared sh;
   __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
   __shared__ RowStat s_stat[kFastMaxG];  // exact statistics of this list's heads (group-sum: all G)
@@ -445,6 +445,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams 
   bitmap_compact(bitmap, n_words, S, kept + S, k, sh.wave_tot);
 }
 
+template <int DT>
+__global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams p) {
+  topk_cand_body<DT, false>(p);
+}
+
+// Per-query lists: G workgroups per row.  Registers are capped so that two workgroups share a CU
+// (8 waves per SIMD): the kernel is a chain of dependent memory round trips, a second resident
+// workgroup fills the waits.
+template <int DT>
+__global__ __launch_bounds__(kTopkThreads, 8) void topk_cand_pq_kernel(TopkCandParams p) {
+  topk_cand_body<DT, true>(p);
+}
+
 }  // namespace
 
 hipError_t launch_sample(const SampleParams& p, hipStream_t s) {
@@ -465,14 +478,14 @@ hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s) {
   if (lds > 64 * 1024 || p.geo.G > kFastMaxG) return hipErrorInvalidValue;
   static uint64_t done_one = 0, done_pq = 0;
   const hipError_t e = p.n_lists > 1
-                           ? allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16, true>, 64 * 1024, &done_pq)
-                           : allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16, false>, 64 * 1024, &done_one);
+                           ? allow_dynamic_lds((const void*)topk_cand_pq_kernel<DT_BF16>, 64 * 1024, &done_pq)
+                           : allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16>, 64 * 1024, &done_one);
   if (e != hipSuccess) return e;
   const dim3 grid((unsigned)(rows * p.n_lists));
   if (p.n_lists > 1)
-    hipLaunchKernelGGL((topk_cand_kernel<DT_BF16, true>), grid, dim3(kTopkThreads), lds, s, p);
+    hipLaunchKernelGGL(topk_cand_pq_kernel<DT_BF16>, grid, dim3(kTopkThreads), lds, s, p);
   else
-    hipLaunchKernelGGL((topk_cand_kernel<DT_BF16, false>), grid, dim3(kTopkThreads), lds, s, p);
+    hipLaunchKernelGGL(topk_cand_kernel<DT_BF16>, grid, dim3(kTopkThreads), lds, s, p);
   return hipGetLastError();
 }
 
