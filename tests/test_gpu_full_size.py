@@ -241,3 +241,22 @@ def test_C5_length_dense_path(ref):
     sk.sagekv_select(desc, q_last, K, V, Kc, Vc, kept2, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(kept2, kept)
+
+
+@pytest.mark.parametrize("scale", [5.0, 12.0, 40.0])
+def test_peaked_attention_at_full_length(ref, scale):
+    """Queries scaled until a handful of tokens hold the whole softmax (logits of magnitude up to
+    ~150): each head's normaliser is then a sum of very few fp32-rounded terms, the case where its error
+    is largest.  64 rows of L = 131072 in the C3 split, every kept set and the gathered K/V against the oracle."""
+    P, Hq, Hkv, d, L, S, W, k = 8, 32, 8, 128, 131072, 4, 512, 3580
+    key = synth.stream_key(4242, 55)
+    q = synth.fill_host(key, 0, P * Hq * d, 0).reshape(P, Hq, d)
+    q = synth.round_to_dtype(scale * synth.to_f64(q, 0), 0)
+    K = synth.fill_host(key, 1 << 30, P * Hkv * L * d, 0).reshape(P, Hkv, L, d)
+    V = synth.fill_host(key, 1 << 33, P * Hkv * L * d, 0).reshape(P, Hkv, L, d)
+    Kc_r, Vc_r, kept_r, s_r = ref.select(0, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    out = gu.gpu_select(0, q, K, V, S, W, k, want_scores=False)
+    print(f"scale {scale}: rows redone by the dense path: {out['redone']} of {P * Hkv}", flush=True)
+    if gu.check_kept(out["kept"], kept_r, s_r[:, :, 0], S, W, k) == 0:
+        np.testing.assert_array_equal(out["Kc"], Kc_r)
+        np.testing.assert_array_equal(out["Vc"], Vc_r)
