@@ -95,7 +95,7 @@ struct SelectLayout {
   bool small;
   size_t logits, scores, partials, stats, ghist, total;
   // pre-filtered path
-  size_t samp_logit, samp_stats, samp_tau, cand_count, ovf_count, cand_idx, cand_logit, cand_score, cand_pos,
+  size_t samp_logit, samp_stats, samp_tau, list_info, cand_count, ovf_count, cand_idx, cand_logit, cand_score, cand_pos,
       row_fail, n_fail;
   int64_t slots_per_row, cs_pitch;
   FastPlan fast;
@@ -163,6 +163,7 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
     l.samp_logit = take(rows * ns * f.Gs * sizeof(float));
     l.samp_stats = take(rows * l.G * sizeof(float2));
     l.samp_tau = take(rows * l.n_lists * sizeof(float));
+    l.list_info = take(rows * l.n_lists * sizeof(float2));
     l.slots_per_row = (int64_t)l.n_chunks * f.cap_c + f.cap;
     l.cand_count = take(rows * l.n_chunks * sizeof(int));
     l.ovf_count = take(rows * sizeof(int));
@@ -575,6 +576,7 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     cp.cand_score = (float*)(ws + l.cand_score);
     cp.cand_pos = (int32_t*)(ws + l.cand_pos);
     cp.cs_pitch = l.cs_pitch;
+    cp.list_info = (float2*)(ws + l.list_info);
     cp.cap = f.cap;
     cp.Gs = f.Gs;
     cp.n_lists = l.n_lists;

@@ -264,6 +264,7 @@ struct TopkCandParams {
   int32_t* cand_pos;         // [rows * n_lists][cs_pitch] scratch: their token indices
   int64_t cs_pitch;          // floats between the lists' scratch rows (>= cap)
   int cap, Gs;               // cap: candidates a row may have; more = redo
+  float2* list_info;         // per-query lists, [rows * n_lists]: (count as int bits, bound), between the two launches
   int n_lists;               // 1 or G: list g of a row ranks head g's own probability
   const void* q_last;
   const void* K;

@@ -215,98 +215,107 @@ __device__ __forceinline__ void flag_row(const TopkCandParams& p, int row, int r
   if (atomicExch(&p.row_fail[row], reason) == 0) atomicAdd(p.n_fail, 1);
 }
 
-// PQ: per-query lists (n_lists = G > 1), each list keeps its own compacted candidates.
-template <int DT, bool PQ>
-__device__ __forceinline__ void topk_cand_body(const TopkCandParams& p) {
-  __shared__ TopkShared sh;
-  __shared__ float sM[kFastMaxG], sInv[kFastMaxG];
-  __shared__ RowStat s_stat[kFastMaxG];  // exact statistics of this list's heads (group-sum: all G)
-  __shared__ double s_rho[kFastMaxG], s_flushed[kFastMaxG];
-  __shared__ int band_j[kMaxBand], band_tok[kMaxBand];
-  __shared__ float band_v[kMaxBand];
-  __shared__ int n_band, n_above, n_list;
-  extern __shared__ __align__(16) uint32_t bitmap[];  // one bit per eviction candidate of the row
+// Shared state of the candidate selection kernels.
+struct CandShared {
+  TopkShared sh;
+  float sM[kFastMaxG], sInv[kFastMaxG];
+  RowStat stat[kFastMaxG];  // exact statistics of the row's heads
+  double rho[kFastMaxG], flushed[kFastMaxG];
+  float bound[kFastMaxG];   // per-query lists: the bound of each head's list,
+  float thr[kFastMaxG];     // and the same bound as a logit of that head
+  int n_list[kFastMaxG];    // per-query lists: candidates each list has kept
+  int band_j[kMaxBand], band_tok[kMaxBand];
+  float band_v[kMaxBand];
+  int n_band, n_above;
+  int chunk_off[1025];
+  int raw_total;
+};
 
-  const int list = blockIdx.x, tid = threadIdx.x;  // one list per row, or one per (row, query head)
-  const int row = list / p.n_lists, gl = list % p.n_lists;
-  const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
+// First half, one workgroup per row: sink and recent indices, the exact softmax statistics of the row's
+// heads, and the candidates' scratch lists.  One list per row (PQ false): cand_score / cand_pos get the
+// exact fp32 score and the token of every candidate; *bound = the bound on a dropped token's score,
+// *n_c = the number of candidates.  Per-query lists (PQ): the row's shared candidate records are read
+// once and list g gets the LOGIT of head g and the token of every candidate that can reach the list's
+// bound (s.bound[g], counts in s.n_list[g]).  False: nothing to select (k = 0) or the row was flagged.
+template <int DT, bool PQ>
+__device__ __forceinline__ bool cand_lists(const TopkCandParams& p, CandShared& s, int row, float* bound, int* n_c) {
+  const int tid = threadIdx.x;
   const int S = p.S, W = p.W, k = p.k, G = p.geo.G;
-  const int g_lo = p.n_lists > 1 ? gl : 0, g_hi = p.n_lists > 1 ? gl + 1 : G;
-  const int64_t L = p.geo.L, E = L - S - W;
+  const int64_t L = p.geo.L;
   const int n_kept = S + p.n_lists * k + W;
   int32_t* kept_row = p.kept_idx + (int64_t)row * n_kept;
-  int32_t* kept = kept_row + gl * k;  // this list's k slots start at kept[S]
 
-  if (gl == 0) {
-    for (int t = tid; t < S; t += kTopkThreads) kept_row[t] = t;
-    for (int t = tid; t < W; t += kTopkThreads) kept_row[S + p.n_lists * k + t] = (int32_t)(L - W + t);
-  }
-  // the dense stages that redo a flagged row add to this list's first-digit histogram
-  for (int b = tid; b < kHistBins; b += kTopkThreads) p.ghist[(int64_t)list * kHistBins + b] = 0;
+  for (int t = tid; t < S; t += kTopkThreads) kept_row[t] = t;
+  for (int t = tid; t < W; t += kTopkThreads) kept_row[S + p.n_lists * k + t] = (int32_t)(L - W + t);
+  // the dense stages that redo a flagged row add to its lists' first-digit histograms
+  for (int b = tid; b < kHistBins * p.n_lists; b += kTopkThreads) p.ghist[(int64_t)row * p.n_lists * kHistBins + b] = 0;
 
-  // Exact softmax statistics of this list's heads, one wave per head, from the partials of the
+  // Exact softmax statistics of the row's heads, one wave per head, from the partials of the
   // filtering pass; and how far the sampled statistics were off: rho = (exact weight) / (sampled weight).
   {
-    const int wave = tid >> 6, g = g_lo + wave;
-    if (g < g_hi) {
+    const int g = tid >> 6;
+    if (g < G) {
       const RowStat st = merge_partials_wave(p.partials + ((int64_t)row * G + g) * p.n_chunks, p.n_chunks);
       if ((tid & 63) == 0) {
-        s_stat[g] = st;
-        sM[g] = st.M;
-        sInv[g] = st.invZ;
+        s.stat[g] = st;
+        s.sM[g] = st.M;
+        s.sInv[g] = st.invZ;
         p.stats[(int64_t)row * G + g] = st;
         const float2 ss = p.samp_stats[(int64_t)row * G + g];
-        s_rho[g] = exp((double)ss.x - (double)st.M) / (st.Z * (double)ss.y);
-        s_flushed[g] = 0x1p-126 * (double)ss.y;  // the filter's exponentials come out as 0 below 2^-126
+        s.rho[g] = exp((double)ss.x - (double)st.M) / (st.Z * (double)ss.y);
+        s.flushed[g] = 0x1p-126 * (double)ss.y;  // the filter's exponentials come out as 0 below 2^-126
       }
     }
   }
-  if (k == 0) return;
+  if (k == 0) return false;
 
   // candidates per score chunk -> offsets of a dense list: the chunks' own slots first, the row's
   // overflow pool behind them
-  __shared__ int chunk_off[1025];
-  __shared__ int s_raw_total;
   const int* cnt = p.cand_count + (int64_t)row * p.n_chunks;
   {
     const int raw = tid < p.n_chunks ? cnt[tid] : 0;
     const int v = raw < p.cap_c ? raw : p.cap_c;
     int tot, raw_tot;
-    const int incl = block_scan_incl<kTopkThreads>(v, sh.wave_tot, &tot);
-    if (tid < p.n_chunks) chunk_off[tid] = incl - v;
-    if (tid == 0) chunk_off[p.n_chunks] = tot;
-    block_scan_incl<kTopkThreads>(raw, sh.wave_tot, &raw_tot);
-    if (tid == 0) s_raw_total = raw_tot;
+    const int incl = block_scan_incl<kTopkThreads>(v, s.sh.wave_tot, &tot);
+    if (tid < p.n_chunks) s.chunk_off[tid] = incl - v;
+    if (tid == 0) s.chunk_off[p.n_chunks] = tot;
+    block_scan_incl<kTopkThreads>(raw, s.sh.wave_tot, &raw_tot);
+    if (tid == 0) s.raw_total = raw_tot;
   }
-  if (tid == 0) n_band = n_above = n_list = 0;
+  if (tid == 0) s.n_band = s.n_above = 0;
+  if (tid < kFastMaxG) s.n_list[tid] = 0;
   __syncthreads();
   // A token the filter dropped had approximate score < tau^, so its exact score is below rho * tau^
-  // (plus what exponentials flushed to zero could hide, plus fp32 slack), rho the worst head's.
-  float bound;
-  {
-    double rho = 0.0, fl = 0.0;
-    for (int g = g_lo; g < g_hi; ++g) {
-      const double r = s_rho[g];
-      rho = r > rho || !(r == r) ? r : rho;
-      fl += s_flushed[g];
+  // (plus what exponentials flushed to zero could hide, plus fp32 slack), rho the worst head's; a
+  // per-query list has its own head's.
+  if (PQ) {
+    if (tid < G) {
+      const double bd = s.rho[tid] * ((double)p.samp_tau[(int64_t)row * G + tid] + s.flushed[tid]) * 1.001;
+      s.bound[tid] = (float)bd;
+      // exp(x - M) / Z >= bd  <=>  x >= M + log(bd Z); lowered by more than fp32 rounding can move either side
+      s.thr[tid] = (float)((double)s.stat[tid].M + log(bd * s.stat[tid].Z) - 1e-4);
     }
-    bound = (float)(rho * ((double)p.samp_tau[list] + fl) * 1.001);
+  } else {
+    double rho = 0.0, fl = 0.0;
+    for (int g = 0; g < G; ++g) {
+      const double r = s.rho[g];
+      rho = r > rho || !(r == r) ? r : rho;
+      fl += s.flushed[g];
+    }
+    *bound = (float)(rho * ((double)p.samp_tau[row] + fl) * 1.001);
   }
-  const int n_primary = chunk_off[p.n_chunks];
-  const int n_ovf = s_raw_total - n_primary;  // = the row's overflow counter
-  const int n_all = s_raw_total;
+  const int n_primary = s.chunk_off[p.n_chunks];
+  const int n_ovf = s.raw_total - n_primary;  // = the row's overflow counter
+  const int n_all = s.raw_total;
+  *n_c = n_all;
   if (n_all > p.cap || n_all < k || n_ovf > p.cap_o) {  // far more candidates than planned, or the threshold was too high
     if (tid == 0) flag_row(p, row, 1);
-    return;
+    return false;
   }
+  __syncthreads();  // s.thr
 
-  // Exact fp32 scores of the candidates (same arithmetic and order as the dense combine stage).
-  // The list keeps those that reach the bound: a candidate below it is in the same position as a
-  // token the filter dropped (the row is only accepted if the k-th score's band lies above the
-  // bound), and with per-query lists most of the row's shared candidates came in through other heads.
-  constexpr bool compact = PQ;
-  float* cs = p.cand_score + (int64_t)list * p.cs_pitch;
-  int32_t* ci = p.cand_pos + (int64_t)list * p.cs_pitch;
+  float* cs0 = p.cand_score + (int64_t)row * p.n_lists * p.cs_pitch;
+  int32_t* ci0 = p.cand_pos + (int64_t)row * p.n_lists * p.cs_pitch;
   const int64_t row_slots = (int64_t)row * p.slots_per_row;
   const int64_t ovf_base = row_slots + (int64_t)p.n_chunks * p.cap_c;
   for (int d0 = 0; d0 < n_all; d0 += 4 * kTopkThreads) {
@@ -317,85 +326,117 @@ __device__ __forceinline__ void topk_cand_body(const TopkCandParams& p) {
       int lo_c = 0, hi_c = p.n_chunks;  // chunk with chunk_off[ch] <= dj < chunk_off[ch + 1]
       while (hi_c - lo_c > 1) {
         const int mid = (lo_c + hi_c) >> 1;
-        if (chunk_off[mid] <= dj) lo_c = mid; else hi_c = mid;
+        if (s.chunk_off[mid] <= dj) lo_c = mid; else hi_c = mid;
       }
       slot[u] = dj >= n_all ? -1
-                : dj < n_primary ? row_slots + (int64_t)lo_c * p.cap_c + (dj - chunk_off[lo_c])
+                : dj < n_primary ? row_slots + (int64_t)lo_c * p.cap_c + (dj - s.chunk_off[lo_c])
                                  : ovf_base + (dj - n_primary);
     }
-    if constexpr (compact) {  // per-query lists: only this list's head is read
-      float x[4];
-      int32_t ti[4];
+    int32_t ti[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int64_t sl = slot[u] < 0 ? row_slots : slot[u];
-        ti[u] = p.cand_idx[sl];
-        x[u] = p.cand_logit[sl * p.Gs + gl];
-      }
+    for (int u = 0; u < 4; ++u) ti[u] = p.cand_idx[slot[u] < 0 ? row_slots : slot[u]];
+    if constexpr (PQ) {
+      // four heads at a time: their logits are one 16-byte load per candidate
+      for (int g4 = 0; g4 < G; g4 += 4) {
+        float4 lg[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        float a = 0.f;
-        a += exp_times(x[u] - sM[gl], sInv[gl]);
-        const bool keep = slot[u] >= 0 && a >= bound;
-        const unsigned long long bal = __ballot(keep);
-        if (bal) {  // wave-uniform
-          int base = 0;
-          if ((tid & 63) == 0) base = atomicAdd(&n_list, __popcll(bal));
-          base = __shfl(base, 0);
-          if (keep) {
-            const int pos = base + __popcll(bal & ((1ull << (tid & 63)) - 1ull));
-            cs[pos] = a;
-            ci[pos] = ti[u];
+        for (int u = 0; u < 4; ++u)
+          lg[u] = *reinterpret_cast<const float4*>(p.cand_logit + (slot[u] < 0 ? row_slots : slot[u]) * p.Gs + g4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int g = g4 + e;
+          if (g >= G) break;  // workgroup-uniform
+          float* cs = cs0 + (int64_t)g * p.cs_pitch;
+          int32_t* ci = ci0 + (int64_t)g * p.cs_pitch;
+          const float thr = s.thr[g];
+          float x[4];
+          unsigned long long bal[4];
+          int n_wave = 0;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            x[u] = e == 0 ? lg[u].x : e == 1 ? lg[u].y : e == 2 ? lg[u].z : lg[u].w;
+            bal[u] = __ballot(slot[u] >= 0 && x[u] >= thr);
+            n_wave += __popcll(bal[u]);
+          }
+          if (n_wave) {  // wave-uniform
+            int base = 0;
+            if ((tid & 63) == 0) base = atomicAdd(&s.n_list[g], n_wave);
+            base = __shfl(base, 0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              if ((bal[u] >> (tid & 63)) & 1ull) {
+                const int pos = base + __popcll(bal[u] & ((1ull << (tid & 63)) - 1ull));
+                cs[pos] = x[u];
+                ci[pos] = ti[u];
+              }
+              base += __popcll(bal[u]);
+            }
           }
         }
       }
     } else {
-    // one list per row: nearly every candidate reaches the bound, they stay in place
-    float4 lg[4][kFastMaxG / 4];
-    int32_t ti[4];
+      // exact fp32 scores, same arithmetic and order as the dense combine stage; nearly every candidate
+      // reaches the bound, they stay in place
+      float4 lg[4][kFastMaxG / 4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t sl = slot[u] < 0 ? row_slots : slot[u];
-      ti[u] = p.cand_idx[sl];
-#pragma unroll
-      for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
-        if (g4 * 4 < G) lg[u][g4] = *reinterpret_cast<const float4*>(p.cand_logit + sl * p.Gs + g4 * 4);
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int dj = d0 + u * kTopkThreads + tid;
-      if (dj < n_all) {
-        float a = 0.f;
+      for (int u = 0; u < 4; ++u) {
+        const int64_t sl = slot[u] < 0 ? row_slots : slot[u];
 #pragma unroll
         for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
-          if (g4 * 4 < G) {
-            const float x[4] = {lg[u][g4].x, lg[u][g4].y, lg[u][g4].z, lg[u][g4].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (g4 * 4 + e < G) a += exp_times(x[e] - sM[g4 * 4 + e], sInv[g4 * 4 + e]);
-          }
-        cs[dj] = a;
-        ci[dj] = ti[u];
+          if (g4 * 4 < G) lg[u][g4] = *reinterpret_cast<const float4*>(p.cand_logit + sl * p.Gs + g4 * 4);
       }
-    }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int dj = d0 + u * kTopkThreads + tid;
+        if (dj < n_all) {
+          float a = 0.f;
+#pragma unroll
+          for (int g4 = 0; g4 < kFastMaxG / 4; ++g4)
+            if (g4 * 4 < G) {
+              const float x[4] = {lg[u][g4].x, lg[u][g4].y, lg[u][g4].z, lg[u][g4].w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (g4 * 4 + e < G) a += exp_times(x[e] - s.sM[g4 * 4 + e], s.sInv[g4 * 4 + e]);
+            }
+          cs0[dj] = a;
+          ci0[dj] = ti[u];
+        }
+      }
     }
   }
   __syncthreads();
-  const int n_c = compact ? n_list : n_all;
+  return true;
+}
+
+// Second half, one workgroup per list: the k best of the list's n_c candidates (cs: scores, or with
+// `logits` the logits of head g_lo, turned into scores here; ci: tokens), certified against `bound`:
+// every token outside the list scores below it.  s.stat[g_lo .. g_hi), s.sM, s.sInv hold the heads'
+// statistics, s.n_band = s.n_above = 0; `kept` = the list's k output slots.
+template <int DT>
+__device__ __forceinline__ void select_list(const TopkCandParams& p, CandShared& s, uint32_t* bitmap, int row, int g_lo,
+                                            int g_hi, float* cs, const int32_t* ci, int n_c, float bound, bool logits,
+                                            int32_t* kept) {
+  const int tid = threadIdx.x;
+  const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
+  const int S = p.S, k = p.k;
+  const int64_t E = p.geo.L - S - p.W;
   if (n_c < k) {
     if (tid == 0) flag_row(p, row, 2);
     return;
   }
-
+  if (logits) {  // exact fp32 scores, same arithmetic as the dense stages
+    const float M = s.sM[g_lo], inv = s.sInv[g_lo];
+    for (int j = tid; j < n_c; j += kTopkThreads) cs[j] = exp_times(cs[j] - M, inv);
+    __syncthreads();
+  }
   // coarse k-th score, then the candidates within the band around it are re-scored in fp64 and
   // ranked exactly (score descending, index ascending); everything above the band is selected
   uint32_t tau;
   int quota;
-  radix_select(sh, cs, n_c, k, false, &tau, &quota);
+  radix_select(s.sh, cs, n_c, k, false, &tau, &quota);
   const float tf = __uint_as_float(tau);
   const float lo = tf * (1.0f - p.band) - kDenormSlack, hi = tf * (1.0f + p.band) + kDenormSlack;
-  // every token outside the list scores below bound[row]: the row is certified only if no such
-  // token can reach the band
+  // the row is certified only if no token outside the list can reach the band
   if (!(lo * (1.0f - p.band) > bound)) {
     if (tid == 0) flag_row(p, row, 3);
     return;
@@ -411,51 +452,91 @@ __device__ __forceinline__ void topk_cand_body(const TopkCandParams& p) {
       const int pos = ci[j] - S;
       atomicOr(&bitmap[pos >> 5], 1u << (pos & 31));
     } else if (j < n_c && v >= lo) {
-      const int t = atomicAdd(&n_band, 1);
-      if (t < kMaxBand) band_j[t] = j;
+      const int t = atomicAdd(&s.n_band, 1);
+      if (t < kMaxBand) s.band_j[t] = j;
     }
     const unsigned long long bal = __ballot(above);
-    if ((tid & 63) == 0 && bal) atomicAdd(&n_above, __popcll(bal));
+    if ((tid & 63) == 0 && bal) atomicAdd(&s.n_above, __popcll(bal));
   }
   __syncthreads();
-  const int nb = n_band, r = k - n_above;
+  const int nb = s.n_band, r = k - s.n_above;
   if (nb > kMaxBand || r < 1 || r > nb) {  // a degenerate row of (nearly) equal scores: dense path
     if (tid == 0) flag_row(p, row, 4);
     return;
   }
   for (int t = tid >> 6; t < nb; t += kTopkWaves) {
-    const int tok = ci[band_j[t]];
-    const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, s_stat, prob, c,
+    const int tok = ci[s.band_j[t]];
+    const float v = refined_score_wave<DT>(p.geo, p.q_last, p.K, p.pm, p.ks_problem, p.ks_head, p.ks_token, s.stat, prob, c,
                                            tok, g_lo, g_hi);
     if ((tid & 63) == 0) {
-      band_v[t] = v;
-      band_tok[t] = tok;
+      s.band_v[t] = v;
+      s.band_tok[t] = tok;
     }
   }
   __syncthreads();
   for (int t = tid; t < nb; t += kTopkThreads) {
-    const float v = band_v[t];
-    const int tok = band_tok[t];
+    const float v = s.band_v[t];
+    const int tok = s.band_tok[t];
     int rank = 0;
-    for (int u = 0; u < nb; ++u) rank += band_v[u] > v || (band_v[u] == v && band_tok[u] < tok);
+    for (int u = 0; u < nb; ++u) rank += s.band_v[u] > v || (s.band_v[u] == v && s.band_tok[u] < tok);
     if (rank < r) atomicOr(&bitmap[(tok - S) >> 5], 1u << ((tok - S) & 31));
   }
   __syncthreads();
-
-  bitmap_compact(bitmap, n_words, S, kept + S, k, sh.wave_tot);
+  bitmap_compact(bitmap, n_words, S, kept + S, k, s.sh.wave_tot);
 }
 
+// One list per row: both halves in one workgroup.
 template <int DT>
 __global__ __launch_bounds__(kTopkThreads) void topk_cand_kernel(TopkCandParams p) {
-  topk_cand_body<DT, false>(p);
+  __shared__ CandShared s;
+  extern __shared__ __align__(16) uint32_t bitmap[];  // one bit per eviction candidate of the row
+  const int row = blockIdx.x;
+  float bound = 0.f;
+  int n_c = 0;
+  if (!cand_lists<DT, false>(p, s, row, &bound, &n_c)) return;
+  select_list<DT>(p, s, bitmap, row, 0, p.geo.G, p.cand_score + (int64_t)row * p.cs_pitch,
+                  p.cand_pos + (int64_t)row * p.cs_pitch, n_c, bound, false,
+                  p.kept_idx + (int64_t)row * (p.S + p.k + p.W));
 }
 
-// Per-query lists: G workgroups per row.  Registers are capped so that two workgroups share a CU
-// (8 waves per SIMD): the kernel is a chain of dependent memory round trips, a second resident
-// workgroup fills the waits.
+// Per-query lists, first launch: one workgroup per row splits the row's candidates into the lists
+// (a list re-reading all of the row's records costs more than everything else it does) and leaves
+// each list's count and bound in list_info; count -1: nothing to select for this row.
+// Registers are capped in both launches so that two workgroups share a CU (8 waves per SIMD): the
+// kernels are chains of dependent memory round trips, a second resident workgroup fills the waits.
+template <int DT>
+__global__ __launch_bounds__(kTopkThreads, 8) void cand_split_pq_kernel(TopkCandParams p) {
+  __shared__ CandShared s;
+  const int row = blockIdx.x, G = p.geo.G;
+  float bound = 0.f;
+  int n_c = 0;
+  const bool ok = cand_lists<DT, true>(p, s, row, &bound, &n_c);  // its exits are workgroup-uniform
+  if ((int)threadIdx.x < G)
+    p.list_info[(int64_t)row * G + threadIdx.x] = make_float2(__int_as_float(ok ? s.n_list[threadIdx.x] : -1),
+                                                               s.bound[threadIdx.x]);
+}
+
+// Per-query lists, second launch: one workgroup per (row, head).
 template <int DT>
 __global__ __launch_bounds__(kTopkThreads, 8) void topk_cand_pq_kernel(TopkCandParams p) {
-  topk_cand_body<DT, true>(p);
+  __shared__ CandShared s;
+  extern __shared__ __align__(16) uint32_t bitmap[];
+  const int list = blockIdx.x, G = p.geo.G;
+  const int row = list / G, g = list % G;
+  const float2 info = p.list_info[list];
+  const int n_c = __float_as_int(info.x);
+  if (n_c < 0) return;
+  if (threadIdx.x == 0) {
+    const RowStat st = p.stats[(int64_t)row * G + g];
+    s.stat[g] = st;
+    s.sM[g] = st.M;
+    s.sInv[g] = st.invZ;
+    s.n_band = s.n_above = 0;
+  }
+  __syncthreads();
+  select_list<DT>(p, s, bitmap, row, g, g + 1, p.cand_score + (int64_t)list * p.cs_pitch,
+                  p.cand_pos + (int64_t)list * p.cs_pitch, n_c, info.y, true,
+                  p.kept_idx + (int64_t)row * (p.S + G * p.k + p.W) + g * p.k);
 }
 
 }  // namespace
@@ -481,11 +562,12 @@ hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s) {
                            ? allow_dynamic_lds((const void*)topk_cand_pq_kernel<DT_BF16>, 64 * 1024, &done_pq)
                            : allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16>, 64 * 1024, &done_one);
   if (e != hipSuccess) return e;
-  const dim3 grid((unsigned)(rows * p.n_lists));
-  if (p.n_lists > 1)
-    hipLaunchKernelGGL(topk_cand_pq_kernel<DT_BF16>, grid, dim3(kTopkThreads), lds, s, p);
-  else
-    hipLaunchKernelGGL(topk_cand_kernel<DT_BF16>, grid, dim3(kTopkThreads), lds, s, p);
+  if (p.n_lists > 1) {
+    hipLaunchKernelGGL(cand_split_pq_kernel<DT_BF16>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
+    hipLaunchKernelGGL(topk_cand_pq_kernel<DT_BF16>, dim3((unsigned)(rows * p.n_lists)), dim3(kTopkThreads), lds, s, p);
+  } else {
+    hipLaunchKernelGGL(topk_cand_kernel<DT_BF16>, dim3((unsigned)rows), dim3(kTopkThreads), lds, s, p);
+  }
   return hipGetLastError();
 }
 
