@@ -15,6 +15,9 @@
 //                     it, then an LDS bitmap turns the unordered selection into ascending positions.  The
 //                     row is only accepted if its k-th score clears the bound, i.e. if no dropped token
 //                     could have been selected; otherwise it is flagged and the dense stages redo it.
+//   cand_split_pq_kernel + topk_cand_pq_kernel
+//                     the same for one list per query head: a workgroup per row splits the row's candidates
+//                     into the heads' lists, then a workgroup per (row, head) selects its list.
 #include "device_utils.h"
 #include "kernels.h"
 #include "radix_select.h"
