@@ -577,6 +577,68 @@ def test_invalid_arguments_are_rejected_before_launch():
     assert float(out.max()) == -7.0  # nothing written
 
 
+def test_many_rows_in_one_call(ref):
+    """64000 rows of a short cache in one call (the largest row counts a call takes: rows index a grid
+    dimension): the eviction pass against the oracle on every row, then decode steps on the reduced cache."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    P, Hq, Hkv, d, L, S, W, k = 8000, 8, 8, 64, 72, 2, 6, 9
+    q, K, V = rand_case(31337, P, Hq, Hkv, d, L, BF16)
+    out, (Kc_r, Vc_r, kept_r, s_r) = select_parity(ref, BF16, q, K, V, S, W, k)
+    Bt = S + k + W
+    # decode is compared where the kept sets are identical (all rows, but for a near-tie swap the contract allows)
+    same = (out["kept"] == kept_r).reshape(P, -1).all(axis=1)
+    assert same.mean() > 0.999
+    ddesc = sk.decode_desc(P, Hq, Hkv, d, BF16, S, k, W, Bt)
+    dws = torch.empty(max(sk.sagekv_decode_workspace_bytes(ddesc), 16), dtype=torch.uint8, device="cuda")
+    res = torch.empty((P, Hq, d), dtype=torch.float32, device="cuda")
+    key = synth.stream_key(31338, 7)
+    for t in range(W + 1):  # once around the recent ring
+        qs = synth.fill_host(key, t * 3 << 24, P * Hq * d, BF16).reshape(P, Hq, d)
+        kn = synth.fill_host(key, (t * 3 + 1) << 24, P * Hkv * d, BF16).reshape(P, Hkv, d)
+        vn = synth.fill_host(key, (t * 3 + 2) << 24, P * Hkv * d, BF16).reshape(P, Hkv, d)
+        sk.sagekv_decode_step(ddesc, *(synth.host_to_torch(x, BF16) for x in (qs, kn, vn)), out["Kc_dev"], out["Vc_dev"],
+                              t, res, dws)
+        torch.cuda.synchronize()
+        ref.append(BF16, Kc_r, Vc_r, kn, vn, S + k, W)
+        want = ref.decode_attn(BF16, GROUP_SUM, qs, Kc_r, Vc_r, Bt)
+        assert np.abs(res.cpu().numpy() - want)[same].max() <= gu.DECODE_ATOL[BF16], f"step {t}"
+
+
+def test_row_limit_is_reported():
+    """More than 65535 rows (or selection lists) in one call: SAGEKV_ERR_UNSUPPORTED before any launch."""
+    import torch
+
+    import paper_2503_08879_amd as sk
+
+    P, Hkv, d, L = 8192, 8, 64, 16  # 65536 rows
+    q = torch.zeros((P, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    K = torch.zeros((P, Hkv, L, d), dtype=torch.bfloat16, device="cuda")
+    Kc = torch.zeros((P, Hkv, 8, d), dtype=torch.bfloat16, device="cuda")
+    kept = torch.full((P, Hkv, 8), -7, dtype=torch.int32, device="cuda")
+    desc = sk.select_desc(q, K, K, 2, 2, 4, 8)
+    assert sk.sagekv_select_workspace_bytes(desc) == 0
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sk.SagekvError) as e:
+        sk.sagekv_select(desc, q, K, K, Kc, Kc, kept, None, ws)
+    assert e.value.code == 2
+    ddesc = sk.decode_desc(P, Hkv, Hkv, d, sk.BF16, 2, 4, 2, 8)
+    out = torch.full((P, Hkv, d), -7.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(sk.SagekvError) as e:
+        sk.sagekv_decode_attn(ddesc, q, Kc, Kc, 8, out, ws)
+    assert e.value.code == 2
+    # 16384 rows of 4 per-query lists each are as many lists
+    q4 = torch.zeros((2048, 4 * Hkv, d), dtype=torch.bfloat16, device="cuda")
+    d4 = sk.select_desc(q4, K[:2048], K[:2048], 2, 2, 1, 8, head_mode=sk.PER_QUERY)
+    with pytest.raises(sk.SagekvError) as e:
+        sk.sagekv_select(d4, q4, K[:2048], K[:2048], Kc[:2048], Kc[:2048], kept[:2048], None, ws)
+    assert e.value.code == 2
+    torch.cuda.synchronize()
+    assert int(kept.max()) == -7 and float(out.max()) == -7.0  # nothing written
+
+
 # ----------------------------------------------------------------------------- decode
 def decode_case(ref, dtype, P, Hq, Hkv, d, S, k, W, steps, seed, grow=False, fused=True):
     import torch
