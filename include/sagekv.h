@@ -88,7 +88,7 @@ typedef struct {
  * those; a row whose result cannot be proven equal to the top-k over ALL its candidates is redone
  * by the dense path (every token's score is materialised).  The kept set is the same either way.
  * SAGEKV_SELECT_DENSE forces the dense path for every row; so does a non-null scores_out, an
- * fp32 cache, G > 16, more than 524288 candidates per row, or a k so large that the pre-filter
+ * fp32 cache, G > 16, more than 1048576 tokens per row, or a k so large that the pre-filter
  * would have to keep about half of the row (roughly 5 k lists + 8192 > L - S - W). */
 enum { SAGEKV_SELECT_DENSE = 1u };
 

@@ -36,7 +36,7 @@ FastPlan fast_plan(const sagekv_select_desc* d) {
   FastPlan f = {};
   const int G = d->n_q_heads / d->n_kv_heads;
   const int64_t E = d->L - d->n_sink - d->n_recent;
-  f.ok = d->dtype == SAGEKV_BF16 && G <= 16 && d->k > 0 && E <= 524288 && d->L <= 1024 * (int64_t)kScoreChunk &&
+  f.ok = d->dtype == SAGEKV_BF16 && G <= 16 && d->k > 0 && E <= 1048576 && d->L <= 1024 * (int64_t)kScoreChunk &&
          !(d->flags & SAGEKV_SELECT_DENSE);
   if (!f.ok) return f;
   const int lists = d->head_mode == SAGEKV_HEADS_PER_QUERY ? G : 1;

@@ -558,12 +558,13 @@ hipError_t launch_sample(const SampleParams& p, hipStream_t s) {
 hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s) {
   const int rows = p.geo.n_problems * p.geo.Hkv;
   const int64_t E = p.geo.L - p.S - p.W;
+  // the bitmap (one bit per candidate, up to 128 KiB) sits next to about 25 KiB of static LDS; a CU has 160 KiB
   const size_t lds = (size_t)((E + 31) / 32) * 4;
-  if (lds > 64 * 1024 || p.geo.G > kFastMaxG) return hipErrorInvalidValue;
+  if (lds > 128 * 1024 || p.geo.G > kFastMaxG) return hipErrorInvalidValue;
   static uint64_t done_one = 0, done_pq = 0;
   const hipError_t e = p.n_lists > 1
-                           ? allow_dynamic_lds((const void*)topk_cand_pq_kernel<DT_BF16>, 64 * 1024, &done_pq)
-                           : allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16>, 64 * 1024, &done_one);
+                           ? allow_dynamic_lds((const void*)topk_cand_pq_kernel<DT_BF16>, 128 * 1024, &done_pq)
+                           : allow_dynamic_lds((const void*)topk_cand_kernel<DT_BF16>, 128 * 1024, &done_one);
   if (e != hipSuccess) return e;
   if (p.n_lists > 1) {
     hipLaunchKernelGGL(cand_split_pq_kernel<DT_BF16>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);

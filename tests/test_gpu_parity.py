@@ -141,6 +141,28 @@ def test_select_row_longer_than_the_lds_bitmap(ref):
     select_parity(ref, BF16, q, K, V, S, W, k)
 
 
+def test_prefiltered_path_at_a_million_tokens(ref):
+    """L = 1,000,000: the longest rows the pre-filtered path takes (one bit per candidate in LDS)."""
+    P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 1_000_000, 4, 1024, 7164
+    q, K, V = rand_case(1_000_003, P, Hq, Hkv, d, L, BF16)
+    Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=False)
+    assert out["redone"] == 0  # certified by the pre-filtered path, not redone densely
+    if gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k) == 0:
+        np.testing.assert_array_equal(out["Kc"], Kc)
+        np.testing.assert_array_equal(out["Vc"], Vc)
+    # per-query lists at the same length
+    kq = 1024
+    Kc, Vc, kept, s = ref.select(BF16, 1, q, K, V, S, W, kq, want_scores=True)
+    out = gu.gpu_select(BF16, q, K, V, S, W, kq, want_scores=False, head_mode=1)
+    assert out["redone"] == 0
+    G = Hq // Hkv
+    for g in range(G):
+        got = np.concatenate([out["kept"][:, :, :S], out["kept"][:, :, S + g * kq:S + (g + 1) * kq], out["kept"][:, :, S + G * kq:]], axis=2)
+        want = np.concatenate([kept[:, :, :S], kept[:, :, S + g * kq:S + (g + 1) * kq], kept[:, :, S + G * kq:]], axis=2)
+        gu.check_kept(got, want, s[:, :, g], S, W, kq)
+
+
 def test_select_all_scores_equal_takes_lowest_indices(ref):
     """q = 0: every probability is 1/L, the whole row ties; the first k candidates must win."""
     P, Hq, Hkv, d, L, S, W, k = 1, 8, 2, 128, 6000, 4, 50, 700
