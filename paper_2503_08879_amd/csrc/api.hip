@@ -95,7 +95,7 @@ struct SelectLayout {
   bool small;
   size_t logits, scores, partials, stats, ghist, total;
   // pre-filtered path
-  size_t samp_logit, samp_stats, samp_tau, list_info, cand_count, ovf_count, cand_idx, cand_logit, cand_score, cand_pos,
+  size_t samp_logit, samp_stats, heavy_thr, samp_tau, list_info, cand_count, ovf_count, cand_idx, cand_logit, cand_score, cand_pos,
       row_fail, n_fail;
   int64_t slots_per_row, cs_pitch;
   FastPlan fast;
@@ -162,6 +162,7 @@ SelectLayout select_layout(const sagekv_select_desc* d, bool own_scores) {
     const size_t ns = (size_t)64 * (f.nA + f.nB + f.nC);
     l.samp_logit = take(rows * ns * f.Gs * sizeof(float));
     l.samp_stats = take(rows * l.G * sizeof(float2));
+    l.heavy_thr = take(rows * l.G * sizeof(float));
     l.samp_tau = take(rows * l.n_lists * sizeof(float));
     l.list_info = take(rows * l.n_lists * sizeof(float2));
     l.slots_per_row = (int64_t)l.n_chunks * f.cap_c + f.cap;
@@ -498,13 +499,10 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
   kp.n_lists = l.n_lists;
   kp.band = kBand;
 
-  if (fast) {
-    // ---- pre-filtered path: sample, one filtering pass over K, selection among the candidates
+  // The sample stage: approximate softmax statistics and filter thresholds for the pre-filtered path; both
+  // that path and the two-sweep path take from it which terms of a softmax sum need an fp64 exponent.
+  auto run_sample = [&]() -> hipError_t {
     const FastPlan& f = l.fast;
-    float2* samp_stats = (float2*)(ws + l.samp_stats);
-    float* samp_tau = (float*)(ws + l.samp_tau);
-    int* row_fail = (int*)(ws + l.row_fail);
-
     SampleParams mp = {};
     mp.geo = geo;
     mp.q_last = q_last;
@@ -529,16 +527,28 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     mp.n_lists = l.n_lists;
     mp.Gs = f.Gs;
     mp.samp_logit = (float*)(ws + l.samp_logit);
-    mp.samp_stats = samp_stats;
-    mp.samp_tau = samp_tau;
-    mp.row_fail = row_fail;
+    mp.samp_stats = (float2*)(ws + l.samp_stats);
+    mp.heavy_thr = (float*)(ws + l.heavy_thr);
+    mp.samp_tau = (float*)(ws + l.samp_tau);
+    mp.row_fail = (int*)(ws + l.row_fail);
     mp.ovf_count = (int*)(ws + l.ovf_count);
     mp.n_fail = (int*)(ws + l.n_fail);
     mp.scale = scale;
     t.begin(SAGEKV_STAGE_SAMPLE);
-    e = launch_sample(mp, s);
+    const hipError_t es = launch_sample(mp, s);
     t.end(SAGEKV_STAGE_SAMPLE);
+    return es;
+  };
+
+  if (fast) {
+    // ---- pre-filtered path: sample, one filtering pass over K, selection among the candidates
+    const FastPlan& f = l.fast;
+    float2* samp_stats = (float2*)(ws + l.samp_stats);
+    float* samp_tau = (float*)(ws + l.samp_tau);
+    int* row_fail = (int*)(ws + l.row_fail);
+    e = run_sample();
     if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    sp.heavy_thr = (const float*)(ws + l.heavy_thr);
 
     ScoreParams fp = sp;
     fp.filt.samp_stats = samp_stats;
@@ -612,6 +622,9 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
   } else if (l.small) {
     // ---- every score is asked for, no logit scratch: two sweeps over K (partials, then scores)
+    e = run_sample();  // for heavy_thr (it also clears the flags; the marker below follows it)
+    if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    sp.heavy_thr = (const float*)(ws + l.heavy_thr);
     if (launch_fill_u32(ws + l.n_fail, 1, 0xFFFFFFFFu, s) != hipSuccess) return SAGEKV_ERR_DEVICE;
     t.begin(SAGEKV_STAGE_SCORE);
     e = launch_score(sp, SCORE_PARTIALS, s);
@@ -635,8 +648,22 @@ sagekv_status select_impl(const sagekv_select_desc* d, const PageMap& pm, const 
     e = launch_score(sp, SCORE_LOGITS, s);
     t.end(SAGEKV_STAGE_SCORE);
     if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
+    ExactStatsParams xp = {};
+    xp.geo = geo;
+    xp.partials = partials;
+    xp.logits = sp.logits;
+    xp.n_chunks = l.n_chunks;
+    xp.stats = stats;
+    xp.ghist = ghist;
+    xp.n_lists = l.n_lists;
+    xp.q_last = q_last;
+    xp.K = K;
+    xp.ks_problem = d->k_stride_problem;
+    xp.ks_head = d->k_stride_head;
+    xp.ks_token = d->k_stride_token;
+    xp.pm = pm;
     t.begin(SAGEKV_STAGE_STATS);
-    e = launch_stats(tp, l.rows, s);
+    e = launch_stats_exact(xp, s);
     t.end(SAGEKV_STAGE_STATS);
     if (e != hipSuccess) return SAGEKV_ERR_DEVICE;
     CombineParams cp = {};

@@ -132,6 +132,19 @@ constexpr float kDenormSlack = 0x1p-142f;
 
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269502162933349609375f); }
 
+// Which terms of a head's softmax sum need an fp64 exponent.  An fp32 logit of magnitude |l| carries an
+// absolute error of about 2.5e-7 |l| (measured), its exponential the same relative error eps.  Terms
+// of weight w_i (share of Z) with independent errors put Z off by eps * sqrt(sum w_i^2) <= eps *
+// sqrt(theta) if every term of weight >= theta is exact; theta = (5e-8 / eps)^2 keeps that at 5e-8,
+// under the fp32 rounding of a score.  M, Z: the head's (estimated) maximum logit and sum of
+// exp(l - M); returns the logit whose term has weight theta (+inf: no term qualifies).
+__host__ __device__ inline float heavy_logit_threshold(float M, float Z) {
+  if (!(Z > 0.f) || !(M == M)) return INFINITY;
+  const float mag = fabsf(M) > 4.f ? fabsf(M) : 4.f;
+  const float r = 5e-8f / (2.5e-7f * mag);
+  return M + logf(r * r * Z);
+}
+
 // ---- block-wide inclusive scan of one int per thread (blockDim.x = NT, multiple of 64) ---------
 // `wave_tot` is NT/64 ints of shared memory.  Returns the inclusive prefix; *total gets the block sum.
 template <int NT>

@@ -156,6 +156,11 @@ struct ScoreParams {
   const void* K;
   int64_t ks_problem, ks_head, ks_token;  // elements
   PageMap pm;
+  // [rows][G] or null.  A logit x >= heavy_thr enters its chunk's softmax sum as exp(l - m) with l
+  // recomputed in fp64: an fp32 logit of magnitude |l| is off by about |l| * 2.5e-7, which is the relative
+  // error of its exponential, and a head whose mass sits on a few such tokens would get a normaliser that
+  // is off by as much; two heads' errors differ, and that can reorder group-sum scores a few 1e-6 apart.
+  const float* heavy_thr;
   float* logits;                          // SCORE_LOGITS: [rows][n_chunks][G][kScoreChunk]
   float2* partials;                       // [rows][G][n_chunks]  (max, sum exp(x - max))
   int n_chunks;
@@ -176,6 +181,21 @@ struct StatsParams {
   int* ghist;      // [rows * n_lists][kHistBins], zeroed here (nullable)
   int G, n_chunks;
   int n_lists;     // selection lists per row: 1 (group-sum) or G (per-query)
+};
+
+// One-sweep dense path: exact statistics from the logit scratch (see stats_exact_kernel).
+struct ExactStatsParams {
+  RowGeom geo;
+  const float2* partials;  // [rows][G][n_chunks]: the chunks' maxima are used
+  const float* logits;     // the score pass's scratch
+  int n_chunks;
+  RowStat* stats;          // out [rows][G]
+  int* ghist;              // [rows * n_lists][kHistBins], zeroed here
+  int n_lists;
+  const void* q_last;
+  const void* K;
+  int64_t ks_problem, ks_head, ks_token;
+  PageMap pm;
 };
 
 struct CombineParams {
@@ -229,6 +249,7 @@ struct SampleParams {
   int Gs;               // heads per token in samp_logit (G rounded up to a multiple of 4)
   float* samp_logit;    // [rows][64 * (nA + nB + nC)][Gs] scratch
   float2* samp_stats;   // out [rows][G]
+  float* heavy_thr;     // out [rows][G]: logits at or above it take part in the softmax sum with an fp64 exponent
   float* samp_tau;      // out [rows * n_lists]
   int* row_fail;        // out [rows] = 0
   int* ovf_count;       // out [rows] = 0
@@ -327,6 +348,7 @@ hipError_t launch_score_filter(const ScoreParams& p, hipStream_t s);
 hipError_t launch_topk_cand(const TopkCandParams& p, hipStream_t s);
 hipError_t launch_score(const ScoreParams& p, ScoreMode mode, hipStream_t s);  // any mode but SCORE_FILTER
 hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s);
+hipError_t launch_stats_exact(const ExactStatsParams& p, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 hipError_t launch_topk(const TopkParams& p, hipStream_t s);
 hipError_t launch_gather(const GatherParams& p, hipStream_t s);

@@ -160,7 +160,10 @@ __global__ __launch_bounds__(kTopkThreads) void sample_stats_kernel(SampleParams
       }
       sHeavy[tid] = hh / sInv[tid];  // share of the first estimate that came from heavy tokens
       sInv[tid] = 1.0f / zz;
-      if (blockIdx.y == 0) p.samp_stats[(int64_t)row * G + tid] = make_float2(sM[tid], 1.0f / zz);
+      if (blockIdx.y == 0) {
+        p.samp_stats[(int64_t)row * G + tid] = make_float2(sM[tid], 1.0f / zz);
+        p.heavy_thr[(int64_t)row * G + tid] = heavy_logit_threshold(sM[tid], zz);
+      }
     }
   }
   __syncthreads();

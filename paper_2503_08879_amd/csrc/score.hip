@@ -128,6 +128,27 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
   }
 }
 
+// exp(l - m) for a term the softmax sum takes with an fp64 exponent (ScoreParams::heavy_thr): the logit of
+// the head whose query row is qrow (bf16, D elements) and of token t of the wave's staged block
+// (16-byte chunks, XOR-swizzled as the staging loop wrote them) is recomputed in fp64.  Rare: out of line.
+template <int D>
+__device__ __noinline__ float heavy_term(const uint4* buf, int t, const uint4* qrow, float m) {
+  constexpr int CH = D / 8;
+  double acc = 0.0;
+  for (int kk = 0; kk < CH; ++kk) {
+    const uint4 kb = buf[t * CH + (kk ^ (t & (CH - 1)))];
+    const uint4 qb = qrow[kk];
+    const uint32_t kw[4] = {kb.x, kb.y, kb.z, kb.w}, qw[4] = {qb.x, qb.y, qb.z, qb.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc += (double)__uint_as_float(kw[e] << 16) * (double)__uint_as_float(qw[e] << 16);
+      acc += (double)__uint_as_float(kw[e] & 0xFFFF0000u) * (double)__uint_as_float(qw[e] & 0xFFFF0000u);
+    }
+  }
+  return (float)exp(acc / sqrt((double)D) - (double)m);
+}
+
+
 // bf16 scoring on the matrix cores.  The dot products of a 16-token tile against the group's
 // query heads are one 16x16x(head_dim) product: A = queries (heads in rows, zero padded),
 // B = keys (tokens in columns), fp32 accumulate.  MFMA operands want a lane to hold 8
@@ -229,6 +250,17 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
   // softmax weights of this lane's 4 heads: the sample's (M^, 1/Z^) for the filter, the exact (M, 1/Z)
   // for the scores; the row's filter threshold(s)
   float fM[4] = {0.f, 0.f, 0.f, 0.f}, fInv[4] = {0.f, 0.f, 0.f, 0.f}, ftau = 0.f;
+  // terms with an fp64 exponent (ScoreParams::heavy_thr): the passes that follow a sample stage; the
+  // one-sweep dense pass (SCORE_LOGITS) leaves them to stats_exact_kernel
+  constexpr bool HEAVY = MODE == SCORE_FILTER || MODE == SCORE_PARTIALS;
+  float hthr[4] = {INFINITY, INFINITY, INFINITY, INFINITY};
+  if (HEAVY && p.heavy_thr) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (hbase + r < gb) hthr[r] = p.heavy_thr[(int64_t)row * p.geo.G + p.g0 + hbase + r];
+  }
+  const uint4* q_heads = reinterpret_cast<const uint4*>(
+      (const char*)p.q_last + (((int64_t)prob * p.geo.Hq + c * p.geo.G + p.g0 + hbase) * D) * 2);  // rows of heads hbase + r
   float ftau_h[4] = {INFINITY, INFINITY, INFINITY, INFINITY};  // per-query lists: a threshold per head
   const bool per_head = FILTER && p.filt.n_lists > 1;
   if (FILTER) {
@@ -299,6 +331,7 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
         }
       }
       // lane (j, n), accumulator a, register r: row 4j + r = (tile slot, head), column n = token
+      bool any_heavy = false;
 #pragma unroll
       for (int a = 0; a < NACC; ++a) {
         const int64_t tok = tok_base + (a * TILES + (4 * j) / GPAD) * 16 + n;
@@ -311,7 +344,9 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
           if (tok < L && hbase + r < gb) {
             if (PARTIALS) {
               const float mn = fmaxf(m[r], x);
-              sum[r] = sum[r] * exp_fast(m[r] - mn) + exp_fast(x - mn);
+              const bool hv = HEAVY && x >= hthr[r];  // rare: its term is added below, with an fp64 exponent
+              any_heavy |= hv;
+              sum[r] = sum[r] * exp_fast(m[r] - mn) + (hv ? 0.f : exp_fast(x - mn));
               m[r] = mn;
             }
             if (FILTER) {
@@ -358,6 +393,16 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
               *reinterpret_cast<float4*>(rec) = make_float4(xs[0][a][0], xs[0][a][1], xs[0][a][2], xs[0][a][3]);
             }
           }
+        }
+      }
+      if (HEAVY && __any(any_heavy)) {  // wave-uniform, rare
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) {
+          const int t_local = (a * TILES + (4 * j) / GPAD) * 16 + n;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (tok_base + t_local < L && hbase + r < gb && xs[0][a][r] >= hthr[r])
+              sum[r] += heavy_term<D>(buf, t_local, q_heads + r * (D / 8), m[r]);
         }
       }
     }
@@ -551,6 +596,91 @@ __global__ __launch_bounds__(64) void stats_kernel(StatsParams p) {
   }
 }
 
+// One-sweep dense path: every token's fp32 logit is in scratch, so a head's normaliser is summed from
+// there once its maximum is known: Z = sum_i exp(l_i - M) in fp64, the terms heavy enough for their
+// logit's fp32 error to show in Z (heavy_logit_threshold) with the logit recomputed in fp64 from K.
+// (The pre-filtered and two-sweep paths do the same inside the score kernel, with a threshold from
+// the sample; here nothing is known about the row before the sweep.)  One workgroup per row.
+constexpr int kMaxHeavy = 4096;  // heavy terms per (row, head) taken exactly; beyond: as fp32 terms
+
+template <int DT>
+__global__ __launch_bounds__(kTopkThreads) void stats_exact_kernel(ExactStatsParams p) {
+  __shared__ double red_d[kTopkWaves];
+  __shared__ RowStat s_stat[64];  // up to 64 heads per KV head
+  __shared__ float s_thr[64];
+  __shared__ int heavy_tok[kMaxHeavy];
+  __shared__ int n_heavy;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, row = blockIdx.x;
+  const int G = p.geo.G, D = p.geo.D;
+  const int prob = row / p.geo.Hkv, c = row % p.geo.Hkv;
+  const int64_t L = p.geo.L;
+  for (int b = tid; b < kHistBins * p.n_lists; b += kTopkThreads) p.ghist[(int64_t)row * p.n_lists * kHistBins + b] = 0;
+  // the chunks' maxima and fp32 sums, one wave per head: M, and a Z that stands unless the head has heavy terms
+  for (int g = wave; g < G; g += kTopkWaves) {
+    const RowStat st = merge_partials_wave(p.partials + ((int64_t)row * G + g) * p.n_chunks, p.n_chunks);
+    if (lane == 0) {
+      s_stat[g] = st;
+      s_thr[g] = heavy_logit_threshold(st.M, (float)st.Z);
+    }
+  }
+  __syncthreads();
+  auto block_sum = [&](double v) -> double {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();  // red_d free
+    if (lane == 0) red_d[wave] = v;
+    __syncthreads();
+    double t = 0.0;
+    for (int w = 0; w < kTopkWaves; ++w) t += red_d[w];
+    return t;
+  };
+  for (int g = 0; g < G; ++g) {
+    const float M = s_stat[g].M, thr = s_thr[g];
+    if (!(thr <= M)) continue;  // no term of this head is heavy enough (workgroup-uniform)
+    __syncthreads();            // the previous head's list has been read
+    if (tid == 0) n_heavy = 0;
+    __syncthreads();
+    // the row's logits of this head, four at a time (a chunk's kScoreChunk logits of a head are contiguous)
+    double z = 0.0;
+    for (int64_t t4 = (int64_t)tid * 4; t4 < L; t4 += 4 * kTopkThreads) {
+      const float4 v = *reinterpret_cast<const float4*>(p.logits + logit_index(p.geo, p.n_chunks, row, g, t4));
+      const float x[4] = {v.x, v.y, v.z, v.w};
+      float part = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (t4 + e >= L) break;
+        bool exact = x[e] >= thr;
+        if (exact) {
+          const int i = atomicAdd(&n_heavy, 1);
+          if (i < kMaxHeavy) heavy_tok[i] = (int)(t4 + e); else exact = false;
+        }
+        if (!exact) part += exp_fast(x[e] - M);
+      }
+      z += (double)part;
+    }
+    z = block_sum(z);  // (its barriers also publish heavy_tok)
+    const int nh = n_heavy < kMaxHeavy ? n_heavy : kMaxHeavy;
+    const double inv = 1.0 / sqrt((double)D);
+    const int64_t q_off = ((int64_t)prob * p.geo.Hq + c * G + g) * D;
+    double zh = 0.0;
+    for (int i = wave; i < nh; i += kTopkWaves) {
+      const int64_t k_off = kv_offset(p.pm, p.pm.ks_page, p.ks_problem, p.ks_head, p.ks_token, prob, c, heavy_tok[i]);
+      double acc = 0.0;
+      for (int jj = lane; jj < D; jj += 64) acc += elem_f64<DT>(p.q_last, q_off + jj) * elem_f64<DT>(p.K, k_off + jj);
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
+      if (lane == 0) zh += exp(acc * inv - (double)M);
+    }
+    z += block_sum(zh);
+    if (tid == 0) {
+      s_stat[g].Z = z;
+      s_stat[g].invZ = (float)(1.0 / z);
+    }
+  }
+  __syncthreads();
+  if (tid < G) p.stats[(int64_t)row * G + tid] = s_stat[tid];
+}
+
 constexpr int kCombineThreads = 256;
 constexpr int kMaxG = 64;
 
@@ -704,6 +834,15 @@ hipError_t launch_score(const ScoreParams& p0, ScoreMode mode, hipStream_t s) {
 
 hipError_t launch_stats(const StatsParams& p, int rows, hipStream_t s) {
   hipLaunchKernelGGL(stats_kernel, dim3((unsigned)rows), dim3(64), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_stats_exact(const ExactStatsParams& p, hipStream_t s) {
+  const int rows = p.geo.n_problems * p.geo.Hkv;
+  if (p.geo.dtype == DT_BF16)
+    hipLaunchKernelGGL(stats_exact_kernel<DT_BF16>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
+  else
+    hipLaunchKernelGGL(stats_exact_kernel<DT_F32>, dim3((unsigned)rows), dim3(kTopkThreads), 0, s, p);
   return hipGetLastError();
 }
 

@@ -402,6 +402,29 @@ def test_select_ranks_scores_below_the_normal_range_prefiltered(ref, head_mode, 
     assert out["redone"] >= 0  # the call went through the pre-filtered path
 
 
+@pytest.mark.parametrize("route", ["prefiltered", "two_sweeps", "one_sweep"])
+def test_group_sum_order_when_few_tokens_hold_a_heads_mass(ref, route):
+    """Queries scaled by 9: one token holds 50-98 % of each head's softmax, with a logit of about 36.
+    An fp32 logit of that size is off by ~1e-5, and so would be a normaliser summed from fp32 logits;
+    the two heads of a group would be off by different amounts, enough to swap group-sum scores that
+    are 2e-6 apart (this case did, at token 145332 of row 1).  The kernels take such terms with an fp64
+    exponent; every route must give the oracle's kept set."""
+    import paper_2503_08879_amd as sk
+
+    P, Hq, Hkv, d, L, S, W, k = 1, 4, 2, 128, 162963, 300, 1, 26083
+    key = synth.stream_key(880000 + 3879, 55)
+    q = synth.fill_host(key, 0, P * Hq * d, BF16).reshape(P, Hq, d)
+    q = synth.round_to_dtype(9.0 * synth.to_f64(q, BF16), BF16)
+    K = synth.fill_host(key, 1 << 30, P * Hkv * L * d, BF16).reshape(P, Hkv, L, d)
+    V = synth.fill_host(key, 1 << 33, P * Hkv * L * d, BF16).reshape(P, Hkv, L, d)
+    Kc, Vc, kept, s = ref.select(BF16, GROUP_SUM, q, K, V, S, W, k, want_scores=True)
+    out = gu.gpu_select(BF16, q, K, V, S, W, k, want_scores=route == "two_sweeps",
+                        flags=sk.SELECT_DENSE if route == "one_sweep" else 0)
+    assert (out["redone"] >= 0) == (route == "prefiltered")
+    assert gu.check_kept(out["kept"], kept, s[:, :, 0], S, W, k) == 0  # no near-tie exemption needed here
+    np.testing.assert_array_equal(out["Kc"], Kc)
+
+
 def test_prefilter_chunk_slots_overflow_into_the_row_pool(ref):
     """Every score chunk owns a few candidate slots; here the heavy tokens all sit in two chunks (as the
     tokens next to the recent window do in a trained model), far more than those chunks' own slots hold,
