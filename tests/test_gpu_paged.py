@@ -27,12 +27,14 @@ def to_pages(X, page_size, table, n_pages, token_major, dtype):
 
 
 def paged_case(ref, dtype, P, Hq, Hkv, d, L, S, W, k, page_size, token_major=False, head_mode=0, want_scores=False,
-               flags=0, seed=0):
+               flags=0, seed=0, q_scale=1.0):
     import torch
 
     import paper_2503_08879_amd as sk
 
     q, K, V = rand_case(900 + seed, P, Hq, Hkv, d, L, dtype)
+    if q_scale != 1.0:  # peaked attention: a few tokens hold each head's softmax
+        q = synth.round_to_dtype(q_scale * synth.to_f64(q, dtype), dtype)
     G = Hq // Hkv
     lists = G if head_mode == 1 else 1
     per = -(-L // page_size)
@@ -143,3 +145,11 @@ def test_paged_arguments_are_checked():
     assert status(block_table=None) == 1 and status(n_pages=0) == 1
     assert status(k_stride_page=ps * d * Hkv + 4) == 2                 # page not 16-byte aligned
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("page,want_scores,flags", [(16, False, 0), (64, True, 0), (256, False, 1)])
+def test_paged_select_with_peaked_attention(ref, page, want_scores, flags):
+    """Queries scaled by 9 over a paged cache: the softmax terms that need an fp64 exponent are recomputed
+    from the staged pages (pre-filtered, two-sweep and one-sweep routes)."""
+    paged_case(ref, BF16, 1, 4, 2, 128, 70001, 4, 65, 9000, page, want_scores=want_scores, flags=flags, seed=41,
+               q_scale=9.0)
