@@ -159,13 +159,31 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
       kv[i] = ld16(ks + cl * 16);
       vv[i] = ld16(vs + cl * 16);
     }
+    // fp32 caches: the logit in fp64 (exact products), and below the exponent's argument from the fp64
+    // logit: an fp32 logit of magnitude 100 would be off by 2.5e-5, and so would its softmax weight
+    constexpr bool F64 = DT == DT_F32;
     float x[SB][GB];
+    double xd[F64 ? SB : 1][F64 ? GB : 1];
 #pragma unroll
     for (int i = 0; i < SB; ++i)
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
         const int tok = t0 + i * TPL + tq;
-        const float v = group_sum<LPT>(dot16<DT>(kv[i], tok < p.qs_S ? q2[g] : q[g], 0.f)) * p.scale;
+        const uint4& qq = tok < p.qs_S ? q2[g] : q[g];
+        float v;
+        if constexpr (F64) {
+          double a = (double)__uint_as_float(kv[i].x) * (double)__uint_as_float(qq.x) +
+                     (double)__uint_as_float(kv[i].y) * (double)__uint_as_float(qq.y) +
+                     (double)__uint_as_float(kv[i].z) * (double)__uint_as_float(qq.z) +
+                     (double)__uint_as_float(kv[i].w) * (double)__uint_as_float(qq.w);
+#pragma unroll
+          for (int o = 1; o < LPT; o <<= 1) a += __shfl_xor(a, o);
+          a *= 1.0 / sqrt((double)D);
+          xd[i][g] = a;
+          v = (float)a;
+        } else {
+          v = group_sum<LPT>(dot16<DT>(kv[i], qq, 0.f)) * p.scale;
+        }
         x[i][g] = valid[i] && head_attends(p.pq_S, p.pq_k, p.G, g0 + g, tok) ? v : -INFINITY;
       }
     float mn[GB];
@@ -193,7 +211,9 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(DecodeParams p, int g0)
         unpack16<DT>(vv[i], vf);
 #pragma unroll
         for (int g = 0; g < GB; ++g) {
-          const float pw = (x[i][g] == -INFINITY) ? 0.f : exp_fast(x[i][g] - mn[g]);
+          float arg = x[i][g] - mn[g];
+          if constexpr (F64) arg = (float)(xd[i][g] - (double)mn[g]);
+          const float pw = (x[i][g] == -INFINITY) ? 0.f : exp_fast(arg);
           l[g] += pw;
 #pragma unroll
           for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw, vf[e], acc[g][e]);

@@ -685,7 +685,7 @@ def test_row_limit_is_reported():
 
 
 # ----------------------------------------------------------------------------- decode
-def decode_case(ref, dtype, P, Hq, Hkv, d, S, k, W, steps, seed, grow=False, fused=True):
+def decode_case(ref, dtype, P, Hq, Hkv, d, S, k, W, steps, seed, grow=False, fused=True, q_scale=1.0):
     import torch
 
     import paper_2503_08879_amd as sk
@@ -701,6 +701,8 @@ def decode_case(ref, dtype, P, Hq, Hkv, d, S, k, W, steps, seed, grow=False, fus
     worst = 0.0
     for t in range(steps):
         q = synth.fill_host(key, (2 << 30) + t * 10_000_000, P * Hq * d, dtype).reshape(P, Hq, d)
+        if q_scale != 1.0:  # peaked attention: logits of magnitude ~4 q_scale
+            q = synth.round_to_dtype(q_scale * synth.to_f64(q, dtype), dtype)
         kn = synth.fill_host(key, (3 << 30) + t * 10_000_000, P * Hkv * d, dtype).reshape(P, Hkv, d)
         vn = synth.fill_host(key, (4 << 30) + t * 10_000_000, P * Hkv * d, dtype).reshape(P, Hkv, d)
         length = ref.append(dtype, Kc, Vc, kn, vn, S + k, W, grow=grow, length=length)
@@ -763,6 +765,15 @@ def test_decode_one_workgroup_per_row(ref, rows, Hq, Hkv, d, S, k, W):
     model's decode step)."""
     P = -(-rows // Hkv)
     decode_case(ref, BF16, P, Hq, Hkv, d, S, k, W, 3, seed=60 + Hq)
+
+
+@pytest.mark.parametrize("dtype", [BF16, F32])
+@pytest.mark.parametrize("q_scale", [9.0, 40.0])
+@pytest.mark.parametrize("rows,Hq,Hkv", [(3, 8, 2), (200, 4, 1)])
+def test_decode_with_peaked_attention(ref, dtype, q_scale, rows, Hq, Hkv):
+    """Scaled queries: logits of magnitude up to ~170, one token holds nearly all of a head's attention.
+    The stated tolerances hold there too (fp32 caches: the kernel takes its logits in fp64)."""
+    decode_case(ref, dtype, max(1, rows // Hkv), Hq, Hkv, 128, 4, 1500, 64, 3, seed=515, q_scale=q_scale)
 
 
 def test_decode_steps_separate_append(ref):
