@@ -130,21 +130,23 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreParams p) {
 
 // exp(l - m) for a term the softmax sum takes with an fp64 exponent (ScoreParams::heavy_thr): the logit of
 // the head whose query row is qrow (bf16, D elements) and of token t of the wave's staged block
-// (16-byte chunks, XOR-swizzled as the staging loop wrote them) is recomputed in fp64.  Rare: out of line.
+// (16-byte chunks, XOR-swizzled as the staging loop wrote them) is recomputed in fp64.  Called by all 64
+// lanes of the wave with the same arguments (two elements per lane); every lane gets the result.
+// Rare: out of line.
 template <int D>
-__device__ __noinline__ float heavy_term(const uint4* buf, int t, const uint4* qrow, float m) {
+__device__ __noinline__ float heavy_term(const uint4* buf, int t, const uint32_t* qrow, float m) {
   constexpr int CH = D / 8;
+  const int lane = threadIdx.x & 63;
   double acc = 0.0;
-  for (int kk = 0; kk < CH; ++kk) {
-    const uint4 kb = buf[t * CH + (kk ^ (t & (CH - 1)))];
-    const uint4 qb = qrow[kk];
-    const uint32_t kw[4] = {kb.x, kb.y, kb.z, kb.w}, qw[4] = {qb.x, qb.y, qb.z, qb.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc += (double)__uint_as_float(kw[e] << 16) * (double)__uint_as_float(qw[e] << 16);
-      acc += (double)__uint_as_float(kw[e] & 0xFFFF0000u) * (double)__uint_as_float(qw[e] & 0xFFFF0000u);
-    }
+  if (lane < D / 2) {
+    const int kk = lane >> 2;  // 16-byte chunk of elements 2 * lane, 2 * lane + 1
+    const uint32_t kw = reinterpret_cast<const uint32_t*>(&buf[t * CH + (kk ^ (t & (CH - 1)))])[lane & 3];
+    const uint32_t qw = qrow[lane];
+    acc = (double)__uint_as_float(kw << 16) * (double)__uint_as_float(qw << 16) +
+          (double)__uint_as_float(kw & 0xFFFF0000u) * (double)__uint_as_float(qw & 0xFFFF0000u);
   }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
   return (float)exp(acc / sqrt((double)D) - (double)m);
 }
 
@@ -259,8 +261,8 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
     for (int r = 0; r < 4; ++r)
       if (hbase + r < gb) hthr[r] = p.heavy_thr[(int64_t)row * p.geo.G + p.g0 + hbase + r];
   }
-  const uint4* q_heads = reinterpret_cast<const uint4*>(
-      (const char*)p.q_last + (((int64_t)prob * p.geo.Hq + c * p.geo.G + p.g0 + hbase) * D) * 2);  // rows of heads hbase + r
+  const uint32_t* q_group = reinterpret_cast<const uint32_t*>(
+      (const char*)p.q_last + (((int64_t)prob * p.geo.Hq + c * p.geo.G + p.g0) * D) * 2);  // query rows of this launch's heads
   float ftau_h[4] = {INFINITY, INFINITY, INFINITY, INFINITY};  // per-query lists: a threshold per head
   const bool per_head = FILTER && p.filt.n_lists > 1;
   if (FILTER) {
@@ -395,14 +397,23 @@ __device__ __forceinline__ void score_mfma_chunk(const ScoreParams& p, int gb, i
           }
         }
       }
-      if (HEAVY && __any(any_heavy)) {  // wave-uniform, rare
+      if (HEAVY && __any(any_heavy)) {  // wave-uniform, rare: the wave takes its heavy terms one at a time
 #pragma unroll
         for (int a = 0; a < NACC; ++a) {
           const int t_local = (a * TILES + (4 * j) / GPAD) * 16 + n;
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (tok_base + t_local < L && hbase + r < gb && xs[0][a][r] >= hthr[r])
-              sum[r] += heavy_term<D>(buf, t_local, q_heads + r * (D / 8), m[r]);
+          for (int r = 0; r < 4; ++r) {
+            unsigned long long todo = __ballot(tok_base + t_local < L && hbase + r < gb && xs[0][a][r] >= hthr[r]);
+            while (todo) {
+              const int src = __ffsll((long long)todo) - 1;  // the lane that holds this (token, head)
+              todo &= todo - 1;
+              const int js = src >> 4, ns = src & 15;
+              const int t_src = (a * TILES + (4 * js) / GPAD) * 16 + ns;
+              const int h_src = (4 * js) % GPAD + r;
+              const float term = heavy_term<D>(buf, t_src, q_group + (int64_t)h_src * (D / 2), __shfl(m[r], src));
+              if (lane == src) sum[r] += term;
+            }
+          }
         }
       }
     }
